@@ -1,0 +1,142 @@
+/*
+ * qspec.h — C ABI of the dual-mode W4 linear layer of QSpec (arXiv 2410.11305)
+ * for AMD MI355X (gfx950).
+ *
+ * One packed 4-bit weight tensor serves two activation modes (paper Sec. 3:
+ * only the activation scheme is switched, no second copy of the weights):
+ *   draft  (W4A4):  qspec_quant_act  ->  qspec_gemm_w4a4
+ *   verify (W4A16): qspec_gemm_w4a16
+ * Quantisation is group-wise along the input dimension K with group size 128
+ * (paper Sec. 4.1, "Implementations").
+ *
+ * Notation: x fp16 [M,K] row-major (tokens x in-features); the weight is
+ * [N,K] (out x in), y = x W^T is fp16 [M,N] row-major; G = K/128.
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer is a DEVICE pointer owned by the caller, 16-byte aligned.
+ *     The library allocates nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  All work is
+ *     enqueued on it; the call returns without synchronising.
+ *   - The return value is a qspec_status.  Arguments are validated on the
+ *     host first; on any error nothing is launched.  No exception or abort
+ *     crosses this boundary.
+ *   - Shapes: group must be 128, K a positive multiple of 128, N a positive
+ *     multiple of 16, M >= 1.  Anything else is QSPEC_ERR_SHAPE.
+ *   - Input and output ranges must not overlap.
+ *   - Non-finite activations: behaviour unspecified.
+ *
+ * Packed weight blob (written by qspec_pack_weights, N*K/2 + N*G*2 bytes)
+ *   codes  : tiles of 16 output rows x 128 input features (one group), 1024
+ *            bytes each, tile (T = n/16, g = k/128) at byte (T*G + g)*1024.
+ *            Inside a tile the 16 bytes at offset 16*(16*kb + n%16) hold the
+ *            32 codes k%128 in [32*kb, 32*kb+32) of row n as four 32-bit
+ *            little-endian words, word i = codes 8i..8i+7 of those 32.  In a
+ *            word the eight 4-bit two's-complement codes c0..c7 sit at bit
+ *            positions 4*p with p = 0..7 holding c0,c2,c4,c6,c1,c3,c5,c7.
+ *   scales : fp16, transposed to [G][N], starting at byte N*K/2.
+ *
+ * Quantised activations (written by qspec_quant_act)
+ *   qa : M rows of K/2 bytes; each aligned run of 8 codes is one 32-bit word
+ *        with the same nibble order as a weight word (c0,c2,c4,c6,c1,c3,c5,c7
+ *        from bit 0 upward).
+ *   sa : fp32 [M][G], row-major.
+ */
+#ifndef QSPEC_H
+#define QSPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  QSPEC_OK = 0,
+  QSPEC_ERR_NULL = 1,        /* a required pointer is NULL                    */
+  QSPEC_ERR_SHAPE = 2,       /* M, N, K or group outside what is supported    */
+  QSPEC_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned              */
+  QSPEC_ERR_WORKSPACE = 4,   /* workspace smaller than qspec_workspace_bytes  */
+  QSPEC_ERR_HIP = 5,         /* the HIP runtime refused the launch            */
+  QSPEC_ERR_UNSUPPORTED = 6  /* the current device is not gfx950              */
+} qspec_status;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* qspec_status_string(int status);
+
+/* Library version: 1000*major + minor. */
+int qspec_version(void);
+
+/* Size in bytes of the packed blob for an [N,K] weight; 0 if the shape is not
+ * supported. */
+size_t qspec_packed_weight_bytes(int N, int K, int group);
+
+/* Scratch the GEMM entry points need for an (M,N,K) problem (partial sums of
+ * K-splits that several workgroups produce); 0 when none is needed.  Returns 0
+ * for unsupported shapes as well (the GEMM call reports those). */
+size_t qspec_workspace_bytes(int M, int N, int K, int group);
+
+/*
+ * Build the shared weight blob (paper Sec. 3: one weight tensor for both
+ * modes; Sec. 4.1: group size 128).  Runs once per layer, off the token path.
+ *   codes      int8 [N,K] row-major, values in [-8,7]; only the low 4 bits of
+ *              each value are stored, out-of-range input is not detected.
+ *   scales_f16 fp16 [N,G] row-major; weight value = code * scale.
+ *   packed     out, qspec_packed_weight_bytes(N,K,group) bytes.
+ */
+int qspec_pack_weights(const int8_t* codes, const void* scales_f16, int N, int K, int group,
+                       void* packed, void* stream);
+
+/* Inverse of qspec_pack_weights (debug / round-trip check): recovers the
+ * canonical int8 [N,K] codes and fp16 [N,G] scales from a blob. */
+int qspec_unpack_weights(const void* packed, int N, int K, int group,
+                         int8_t* codes, void* scales_f16, void* stream);
+
+/*
+ * Activation quantiser of the draft mode (paper Sec. 1: in W4A4 activations
+ * are 4-bit as well).  Per token m and group j, in binary32:
+ *   a = max|x|, s = a / 7 (IEEE division), q = clamp(rne(x / s), -8, 7)
+ * (IEEE division, round half to even); an all-zero group gives s = 0, q = 0.
+ *   x_f16 fp16 [M,K];  qa out, M*K/2 bytes;  sa out, fp32 [M,G].
+ */
+int qspec_quant_act(const void* x_f16, int M, int K, int group,
+                    uint8_t* qa, float* sa, void* stream);
+
+/*
+ * Draft-mode product (paper Sec. 1: W4A4 runs on the low-precision matrix
+ * units without dequantising to a higher precision):
+ *   P[m,n,j] = sum_{k in group j} qa[m,k] * qw[n,k]             (int32, exact)
+ *   y[m,n]   = fp16( sum_j float(P[m,n,j]) * sa[m,j] * sw[n,j] ) (fp32 sums)
+ *   packed  blob from qspec_pack_weights for the same (N,K);
+ *   qa, sa  from qspec_quant_act for the same (M,K);
+ *   y_f16   out, fp16 [M,N];
+ *   workspace  at least qspec_workspace_bytes(M,N,K,group) bytes (may be NULL
+ *              when that is 0); contents are scratch.
+ */
+int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa,
+                    int M, int N, int K, int group,
+                    void* y_f16, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Verify-mode product (paper Sec. 1: W4A16 dequantises the 4-bit weights to
+ * fp16 at run time and multiplies with fp16 activations):
+ *   y[m,n] = fp16( sum_k x[m,k] * qw[n,k] * sw[n, k/128] )       (fp32 sums)
+ *   x_f16 fp16 [M,K]; other arguments as for qspec_gemm_w4a4.
+ */
+int qspec_gemm_w4a16(const void* packed, const void* x_f16,
+                     int M, int N, int K, int group,
+                     void* y_f16, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Debug entry: the exact per-group integer partial sums of the draft product
+ * for output columns n0 .. n0+n_count-1 (n0 and n_count multiples of 16):
+ *   partials[m, n - n0, j] = P[m,n,j], int32 [M, n_count, G] row-major.
+ */
+int qspec_gemm_w4a4_partials(const void* packed, const uint8_t* qa,
+                             int M, int N, int K, int group,
+                             int n0, int n_count, int32_t* partials, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QSPEC_H */

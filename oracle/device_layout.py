@@ -1,0 +1,104 @@
+"""Byte layouts of the device buffers, written out independently of the HIP code.
+
+TEST INFRASTRUCTURE ONLY (see qspec_oracle.py).  The shared weight tensor of
+QSpec (paper Sec. 3: the draft and verify modes read the same 4-bit weights)
+is stored on the GPU as a permutation of the canonical nibble-packed codes
+plus transposed group scales; the activation codes use the same word format.
+These functions restate that layout from its specification so that the blob
+the GPU writes can be compared byte for byte.
+
+Layout specification
+  word   : eight consecutive codes c0..c7 (k = 8w .. 8w+7) as one little-endian
+           32-bit word; 4-bit two's-complement code c_e sits at bit 4*POS[e]
+           with POS = (0, 4, 1, 5, 2, 6, 3, 7).
+  weights: tiles of 16 rows x 128 k (1024 B); tile (T, g) at byte
+           (T*G + g)*1024; inside, the 16 bytes at 16*(16*kb + r) are the four
+           words of row 16T + r covering k%128 in [32kb, 32kb + 32).
+           After all tiles: fp16 scales transposed to [G][N].
+  acts   : row-major, word w of row m at byte m*K/2 + 4w.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+GROUP = 128
+POS = (0, 4, 1, 5, 2, 6, 3, 7)     # bit position / 4 of code e inside its word
+
+
+def _words(codes: np.ndarray) -> np.ndarray:
+    """int8 [R, K] -> uint32 [R, K/8] in the word format above."""
+    R, K = codes.shape
+    if K % 8:
+        raise ValueError("K must be a multiple of 8")
+    nib = (codes.astype(np.int64) & 0xF).reshape(R, K // 8, 8)
+    w = np.zeros((R, K // 8), dtype=np.int64)
+    for e in range(8):
+        w |= nib[:, :, e] << (4 * POS[e])
+    return w.astype(np.uint32)
+
+
+def _codes_from_words(words: np.ndarray) -> np.ndarray:
+    R, W = words.shape
+    w = words.astype(np.int64)
+    out = np.empty((R, W, 8), dtype=np.int64)
+    for e in range(8):
+        out[:, :, e] = (w >> (4 * POS[e])) & 0xF
+    out = np.where(out >= 8, out - 16, out)
+    return out.reshape(R, W * 8).astype(np.int8)
+
+
+def act_bytes(codes: np.ndarray) -> np.ndarray:
+    """int8 codes [M, K] -> uint8 [M, K/2] as the activation quantiser stores them."""
+    words = _words(np.asarray(codes))
+    return words.astype("<u4").view(np.uint8).reshape(codes.shape[0], -1)
+
+
+def decode_act_bytes(qa: np.ndarray) -> np.ndarray:
+    qa = np.ascontiguousarray(qa, dtype=np.uint8)
+    words = qa.view("<u4")
+    return _codes_from_words(words)
+
+
+def weight_blob(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    """int8 codes [N, K], fp16 scales [N, G] -> uint8 blob of N*K/2 + 2*N*G bytes."""
+    codes = np.asarray(codes)
+    scales = np.asarray(scales)
+    N, K = codes.shape
+    if N % 16 or K % GROUP:
+        raise ValueError("N must be a multiple of 16 and K of 128")
+    G = K // GROUP
+    if scales.shape != (N, G) or scales.dtype != np.float16:
+        raise ValueError("scales must be fp16 [N, G]")
+    words = _words(codes)                                   # [N, K/8]
+    # n = 16T + r ; word index = 16g + 4kb + i
+    w5 = words.reshape(N // 16, 16, G, 4, 4)                # [T, r, g, kb, i]
+    tiles = np.ascontiguousarray(w5.transpose(0, 2, 3, 1, 4))   # [T, g, kb, r, i]
+    code_bytes = tiles.astype("<u4").view(np.uint8).reshape(-1)
+    scale_bytes = np.ascontiguousarray(scales.T).view(np.uint8).reshape(-1)
+    return np.concatenate([code_bytes, scale_bytes])
+
+
+def decode_weight_blob(blob: np.ndarray, N: int, K: int):
+    """Inverse of weight_blob -> (int8 codes [N, K], fp16 scales [N, G])."""
+    G = K // GROUP
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    nb = N * K // 2
+    tiles = blob[:nb].view("<u4").reshape(N // 16, G, 4, 16, 4)     # [T, g, kb, r, i]
+    words = np.ascontiguousarray(tiles.transpose(0, 3, 1, 2, 4)).reshape(N, K // 8)
+    scales = blob[nb:nb + 2 * N * G].view(np.float16).reshape(G, N).T
+    return _codes_from_words(words), np.ascontiguousarray(scales)
+
+
+def weight_byte_offset(n: int, k: int, G: int) -> int:
+    """Byte of the blob that holds code (n, k) (scalar form of the same spec,
+    used by the pin that walks the blob code by code)."""
+    T, r = divmod(n, 16)
+    g, kk = divmod(k, GROUP)
+    kb, k32 = divmod(kk, 32)
+    i, e = divmod(k32, 8)
+    return (T * G + g) * 1024 + 16 * (16 * kb + r) + 4 * i + POS[e] // 2
+
+
+def weight_nibble_shift(k: int) -> int:
+    """0 if code k is the low nibble of its byte, 4 if the high nibble."""
+    return 4 * (POS[k % 8] % 2)

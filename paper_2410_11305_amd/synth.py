@@ -1,0 +1,117 @@
+"""Seeded synthetic inputs for the QSpec linear-layer workloads.
+
+This module holds no arithmetic of the method itself: it only draws the
+random tensors (weight codes, weight scales, activations) that both the HIP
+path and the test oracle consume, and lists the layer shapes of the five
+benchmark configurations.  The shapes are the linear layers of Llama-class
+decoder blocks (the models of paper Sec. 4.1 / Table 4), batch sizes 4..128
+and draft lengths gamma = 3 or 5 (Sec. 4.1; Fig. 5 ablation); they stand in
+for the paper's checkpoints and prompt sets, which are not available offline.
+
+Recipe (NumPy PCG64, seed = 10000*config + 100*layer + stream):
+  stream 0  weight codes   integers in [-8, 7], int8 [N, K]
+  stream 1  weight scales  uniform [0.002, 0.01) -> fp16 [N, K/128]
+  stream 2  draft x        N(0,1) fp32 [M_draft, K], outlier channels x20, -> fp16
+  stream 3  verify x       same, [M_verify, K]
+  stream 4  outlier channel indices (without replacement), shared by 2 and 3
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List
+
+import numpy as np
+
+GROUP = 128
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    K: int
+    N: int
+
+
+@dataclass(frozen=True)
+class Config:
+    index: int
+    label: str
+    layers: tuple
+    batch: int
+    gamma: int
+    n_outliers_exact: int = -1      # >= 0: that many outlier channels, else 1 % of K
+
+    @property
+    def draft_M(self) -> int:       # one token per sequence per draft step (Sec. 3.1)
+        return self.batch
+
+    @property
+    def verify_M(self) -> int:      # gamma drafts + 1 per sequence in one pass (Sec. 3.1)
+        return self.batch * (self.gamma + 1)
+
+
+_L7B = (Layer("qkv", 4096, 12288), Layer("o", 4096, 4096),
+        Layer("gate_up", 4096, 22016), Layer("down", 11008, 4096))
+_L13B = (Layer("qkv", 5120, 15360), Layer("o", 5120, 5120),
+         Layer("gate_up", 5120, 27648), Layer("down", 13824, 5120))
+_L70B = (Layer("qkv", 8192, 10240), Layer("o", 8192, 8192),
+         Layer("gate_up", 8192, 57344), Layer("down", 28672, 8192))
+
+CONFIGS: Dict[int, Config] = {
+    1: Config(1, "single-1024", (Layer("lin", 1024, 1024),), 4, 3, n_outliers_exact=4),
+    2: Config(2, "llama7b-b8-g3", _L7B, 8, 3),
+    3: Config(3, "llama7b-b32-g3", _L7B, 32, 3),
+    4: Config(4, "llama13b-b64-g5", _L13B, 64, 5),
+    5: Config(5, "llama70b-b128-g3", _L70B, 128, 3),
+}
+
+
+def _seed(config: int, layer_index: int, stream: int) -> int:
+    return 10000 * config + 100 * layer_index + stream
+
+
+def n_outliers(cfg: Config, K: int) -> int:
+    if cfg.n_outliers_exact >= 0:
+        return cfg.n_outliers_exact
+    return int(round(0.01 * K))
+
+
+def weight_codes(config: int, layer_index: int, N: int, K: int) -> np.ndarray:
+    rng = np.random.default_rng(_seed(config, layer_index, 0))
+    return rng.integers(-8, 8, size=(N, K), dtype=np.int8)
+
+
+def weight_scales(config: int, layer_index: int, N: int, K: int) -> np.ndarray:
+    rng = np.random.default_rng(_seed(config, layer_index, 1))
+    return rng.uniform(0.002, 0.01, size=(N, K // GROUP)).astype(np.float16)
+
+
+def outlier_channels(config: int, layer_index: int, K: int) -> np.ndarray:
+    cfg = CONFIGS[config]
+    rng = np.random.default_rng(_seed(config, layer_index, 4))
+    return np.sort(rng.choice(K, size=n_outliers(cfg, K), replace=False))
+
+
+def activations(config: int, layer_index: int, M: int, K: int, verify: bool) -> np.ndarray:
+    rng = np.random.default_rng(_seed(config, layer_index, 3 if verify else 2))
+    x = rng.standard_normal((M, K), dtype=np.float32)
+    x[:, outlier_channels(config, layer_index, K)] *= np.float32(20.0)
+    return x.astype(np.float16)
+
+
+def generic_case(seed: int, M: int, N: int, K: int, outlier_frac: float = 0.01):
+    """Same recipe for an arbitrary (M, N, K): returns codes, scales, x."""
+    rng = np.random.default_rng(seed)
+    codes = rng.integers(-8, 8, size=(N, K), dtype=np.int8)
+    scales = rng.uniform(0.002, 0.01, size=(N, K // GROUP)).astype(np.float16)
+    x = rng.standard_normal((M, K), dtype=np.float32)
+    n_out = max(1, int(round(outlier_frac * K)))
+    x[:, rng.choice(K, size=n_out, replace=False)] *= np.float32(20.0)
+    return codes, scales, x.astype(np.float16)
+
+
+def layer_table(config: int) -> List[dict]:
+    cfg = CONFIGS[config]
+    return [dict(config=config, layer_index=i, name=l.name, K=l.K, N=l.N,
+                 draft_M=cfg.draft_M, verify_M=cfg.verify_M)
+            for i, l in enumerate(cfg.layers)]
