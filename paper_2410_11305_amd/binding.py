@@ -1,0 +1,184 @@
+"""ctypes binding of libqspec.so: same names as the C ABI (include/qspec.h),
+argument marshalling only.  Tensors are torch CUDA tensors; torch provides the
+device memory and the stream, every computation runs in the HIP library.
+There is no fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqspec.so")
+GROUP = 128
+
+OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED = range(7)
+
+EXPORTS = (
+    "qspec_status_string", "qspec_version", "qspec_packed_weight_bytes", "qspec_workspace_bytes",
+    "qspec_pack_weights", "qspec_unpack_weights", "qspec_quant_act", "qspec_gemm_w4a4",
+    "qspec_gemm_w4a16", "qspec_gemm_w4a4_partials",
+)
+
+
+class QSpecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libqspec.so (built by `python -m paper_2410_11305_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2410_11305_amd.build` "
+            "(there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    L.qspec_status_string.restype = ctypes.c_char_p
+    L.qspec_status_string.argtypes = [ci]
+    L.qspec_version.restype = ci
+    L.qspec_version.argtypes = []
+    L.qspec_packed_weight_bytes.restype = sz
+    L.qspec_packed_weight_bytes.argtypes = [ci, ci, ci]
+    L.qspec_workspace_bytes.restype = sz
+    L.qspec_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    L.qspec_pack_weights.restype = ci
+    L.qspec_pack_weights.argtypes = [vp, vp, ci, ci, ci, vp, vp]
+    L.qspec_unpack_weights.restype = ci
+    L.qspec_unpack_weights.argtypes = [vp, ci, ci, ci, vp, vp, vp]
+    L.qspec_quant_act.restype = ci
+    L.qspec_quant_act.argtypes = [vp, ci, ci, ci, vp, vp, vp]
+    L.qspec_gemm_w4a4.restype = ci
+    L.qspec_gemm_w4a4.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    L.qspec_gemm_w4a16.restype = ci
+    L.qspec_gemm_w4a16.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    L.qspec_gemm_w4a4_partials.restype = ci
+    L.qspec_gemm_w4a4_partials.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().qspec_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return lib().qspec_version()
+
+
+def packed_weight_bytes(N: int, K: int, group: int = GROUP) -> int:
+    return lib().qspec_packed_weight_bytes(N, K, group)
+
+
+def workspace_bytes(M: int, N: int, K: int, group: int = GROUP) -> int:
+    return lib().qspec_workspace_bytes(M, N, K, group)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise QSpecError(status, where)
+
+
+def _workspace(M, N, K, group, workspace):
+    need = workspace_bytes(M, N, K, group)
+    if workspace is None:
+        if need == 0:
+            return None, 0
+        raise ValueError(f"this shape needs a workspace of {need} bytes")
+    return _dev(workspace, torch.uint8, "workspace"), workspace.numel()
+
+
+def pack_weights(codes: torch.Tensor, scales: torch.Tensor, packed: torch.Tensor = None,
+                 group: int = GROUP) -> torch.Tensor:
+    """codes int8 [N,K] in [-8,7], scales fp16 [N,K/128] -> uint8 blob."""
+    N, K = codes.shape
+    if packed is None:
+        nbytes = packed_weight_bytes(N, K, group)
+        if nbytes == 0:
+            raise QSpecError(ERR_SHAPE, "qspec_pack_weights")
+        packed = torch.empty(nbytes, dtype=torch.uint8, device=codes.device)
+    _check(lib().qspec_pack_weights(_dev(codes, torch.int8, "codes"), _dev(scales, torch.float16, "scales"),
+                                    N, K, group, _dev(packed, torch.uint8, "packed"), _stream()),
+           "qspec_pack_weights")
+    return packed
+
+
+def unpack_weights(packed: torch.Tensor, N: int, K: int, group: int = GROUP):
+    codes = torch.empty((N, K), dtype=torch.int8, device=packed.device)
+    scales = torch.empty((N, K // group), dtype=torch.float16, device=packed.device)
+    _check(lib().qspec_unpack_weights(_dev(packed, torch.uint8, "packed"), N, K, group,
+                                      codes.data_ptr(), scales.data_ptr(), _stream()),
+           "qspec_unpack_weights")
+    return codes, scales
+
+
+def quant_act(x: torch.Tensor, qa: torch.Tensor = None, sa: torch.Tensor = None, group: int = GROUP):
+    """x fp16 [M,K] -> (qa uint8 [M,K/2], sa fp32 [M,K/128])."""
+    M, K = x.shape
+    if qa is None:
+        qa = torch.empty((M, K // 2), dtype=torch.uint8, device=x.device)
+    if sa is None:
+        sa = torch.empty((M, max(K // group, 1)), dtype=torch.float32, device=x.device)
+    _check(lib().qspec_quant_act(_dev(x, torch.float16, "x"), M, K, group,
+                                 _dev(qa, torch.uint8, "qa"), _dev(sa, torch.float32, "sa"), _stream()),
+           "qspec_quant_act")
+    return qa, sa
+
+
+def gemm_w4a4(packed: torch.Tensor, qa: torch.Tensor, sa: torch.Tensor, N: int,
+              y: torch.Tensor = None, workspace: torch.Tensor = None, group: int = GROUP) -> torch.Tensor:
+    M, K = qa.shape[0], qa.shape[1] * 2
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=qa.device)
+    ws, ws_bytes = _workspace(M, N, K, group, workspace)
+    _check(lib().qspec_gemm_w4a4(_dev(packed, torch.uint8, "packed"), _dev(qa, torch.uint8, "qa"),
+                                 _dev(sa, torch.float32, "sa"), M, N, K, group,
+                                 _dev(y, torch.float16, "y"), ws, ws_bytes, _stream()),
+           "qspec_gemm_w4a4")
+    return y
+
+
+def gemm_w4a16(packed: torch.Tensor, x: torch.Tensor, N: int, y: torch.Tensor = None,
+               workspace: torch.Tensor = None, group: int = GROUP) -> torch.Tensor:
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    ws, ws_bytes = _workspace(M, N, K, group, workspace)
+    _check(lib().qspec_gemm_w4a16(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"),
+                                  M, N, K, group, _dev(y, torch.float16, "y"), ws, ws_bytes, _stream()),
+           "qspec_gemm_w4a16")
+    return y
+
+
+def gemm_w4a4_partials(packed: torch.Tensor, qa: torch.Tensor, N: int, n0: int, n_count: int,
+                       partials: torch.Tensor = None, group: int = GROUP) -> torch.Tensor:
+    M, K = qa.shape[0], qa.shape[1] * 2
+    if partials is None:
+        partials = torch.empty((M, n_count, K // group), dtype=torch.int32, device=qa.device)
+    _check(lib().qspec_gemm_w4a4_partials(_dev(packed, torch.uint8, "packed"), _dev(qa, torch.uint8, "qa"),
+                                          M, N, K, group, n0, n_count,
+                                          _dev(partials, torch.int32, "partials"), _stream()),
+           "qspec_gemm_w4a4_partials")
+    return partials

@@ -1,0 +1,50 @@
+// Activation quantiser of the draft mode (paper Sec. 1: W4A4 quantises the
+// activations to 4 bit as well; Sec. 4.1: groups of 128).  Per token and
+// group, all in binary32: a = max|x|, s = a / 7, q = clamp(rne(x / s), -8, 7),
+// both divisions IEEE-exact (no reciprocal shortcut), ties to even.
+#pragma once
+#include "common.hpp"
+
+namespace qspec {
+
+// One thread owns 8 consecutive activations (one 16-byte load, one 32-bit
+// code word); 16 adjacent lanes own one group, so the absmax is a 4-step
+// butterfly inside a quarter wavefront and no LDS is needed.
+__global__ __launch_bounds__(256) void quant_act_kernel(const uint4* __restrict__ x,
+                                                        uint32_t* __restrict__ qa_words,
+                                                        float* __restrict__ sa,
+                                                        size_t n_words) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  // n_words is a multiple of 16, so a 16-lane group is entirely in or out of
+  // range; out-of-range lanes still take part in the shuffles below.
+  const bool live = idx < n_words;
+  uint4 raw = {0u, 0u, 0u, 0u};
+  if (live) raw = x[idx];
+  float v[8];
+  {
+    const v8h h = __builtin_bit_cast(v8h, raw);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)h[e];
+  }
+  float a = 0.0f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(v[e]));
+#pragma unroll
+  for (int off = 1; off < 16; off <<= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+  const float s = a / 7.0f;
+  uint32_t w = 0;
+  if (a > 0.0f) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float t = rintf(v[e] / s);                 // v_rndne: ties to even
+      t = fminf(fmaxf(t, -8.0f), 7.0f);
+      w |= ((uint32_t)(int)t & 0xFu) << (4 * nibble_pos(e));
+    }
+  }
+  if (live) {
+    qa_words[idx] = w;
+    if ((threadIdx.x & 15) == 0) sa[idx >> 4] = s;
+  }
+}
+
+}  // namespace qspec

@@ -1,0 +1,71 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/qspec.h declares, and rejects bad arguments before it
+touches the device."""
+import os
+import re
+
+import pytest
+
+from paper_2410_11305_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "qspec.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qspec_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    L = B.lib()
+    names = _declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_size_queries():
+    assert B.version() >= 1000
+    assert B.packed_weight_bytes(1024, 1024) == 1024 * 1024 // 2 + 1024 * 8 * 2
+    assert B.packed_weight_bytes(4096, 11008) == 4096 * 11008 // 2 + 4096 * 86 * 2
+    assert B.packed_weight_bytes(1024, 1000) == 0          # K not a multiple of 128
+    assert B.packed_weight_bytes(1000, 1024) == 0          # N not a multiple of 16
+    assert B.packed_weight_bytes(1024, 1024, 64) == 0      # group size is fixed
+    assert B.workspace_bytes(0, 1024, 1024) == 0
+    for code in range(8):
+        assert B.status_string(code)
+
+
+@pytest.mark.parametrize("fn", ["qspec_gemm_w4a16", "qspec_gemm_w4a4"])
+def test_gemm_argument_validation_without_device(fn):
+    L = B.lib()
+    a = 4096          # any 16-byte aligned non-null address: rejected before use
+    if fn == "qspec_gemm_w4a16":
+        call = lambda packed, act, M, N, K, g, y: L.qspec_gemm_w4a16(packed, act, M, N, K, g, y, None, 0, None)
+    else:
+        call = lambda packed, act, M, N, K, g, y: L.qspec_gemm_w4a4(packed, act, a, M, N, K, g, y, None, 0, None)
+    assert call(None, a, 1, 16, 128, 128, a) == B.ERR_NULL
+    assert call(a, a, 1, 16, 128, 128, None) == B.ERR_NULL
+    assert call(a, a, 0, 16, 128, 128, a) == B.ERR_SHAPE
+    assert call(a, a, 1, 24, 128, 128, a) == B.ERR_SHAPE
+    assert call(a, a, 1, 16, 192, 128, a) == B.ERR_SHAPE
+    assert call(a, a, 1, 16, 128, 64, a) == B.ERR_SHAPE
+    assert call(a, a + 2, 1, 16, 128, 128, a) == B.ERR_ALIGN
+    assert call(a + 8, a, 1, 16, 128, 128, a) == B.ERR_ALIGN
+
+
+def test_other_entries_validate_without_device():
+    L = B.lib()
+    a = 4096
+    assert L.qspec_pack_weights(None, a, 16, 128, 128, a, None) == B.ERR_NULL
+    assert L.qspec_pack_weights(a, a, 8, 128, 128, a, None) == B.ERR_SHAPE
+    assert L.qspec_pack_weights(a, a + 4, 16, 128, 128, a, None) == B.ERR_ALIGN
+    assert L.qspec_unpack_weights(a, 16, 100, 128, a, a, None) == B.ERR_SHAPE
+    assert L.qspec_quant_act(a, 0, 128, 128, a, a, None) == B.ERR_SHAPE
+    assert L.qspec_quant_act(a, 1, 128, 128, None, a, None) == B.ERR_NULL
+    assert L.qspec_quant_act(a + 1, 1, 128, 128, a, a, None) == B.ERR_ALIGN
+    assert L.qspec_gemm_w4a4_partials(a, a, 1, 32, 128, 128, 8, 16, a, None) == B.ERR_SHAPE
+    assert L.qspec_gemm_w4a4_partials(a, a, 1, 32, 128, 128, 16, 32, a, None) == B.ERR_SHAPE
+    assert L.qspec_gemm_w4a4_partials(a, a, 1, 32, 128, 128, 0, 0, a, None) == B.ERR_SHAPE
+    assert L.qspec_gemm_w4a4_partials(a, a, 1, 32, 128, 128, 0, 32, None, None) == B.ERR_NULL
