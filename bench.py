@@ -1,0 +1,287 @@
+#!/usr/bin/env python3
+"""Benchmark of the QSpec W4 linear-layer hot path on one MI355X.
+
+Workload (configuration 2 of the build's table): the four linear layers of a
+Llama-7B-shaped decoder block (qkv 4096->12288, o 4096->4096, gate_up
+4096->22016, down 11008->4096), int4 weights with fp16 group scales (g=128),
+batch 8, draft length gamma=3.  One *step* is one draft pass (activation
+quantiser + W4A4 GEMM at M=8 for every linear) plus one verify pass (W4A16
+GEMM at M=32 for every linear) over `--layers` decoder blocks with distinct
+weight blobs (default 32 = the whole model, 3.3 GB of packed weights, so
+every weight byte comes from HBM and not from the 256 MB last-level cache).
+Weight packing runs once before the timed region (it is off the token path)
+and is reported separately.
+
+Prints ONE JSON line:  value = algorithmic bytes of a step / time, in TB/s.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def alg_bytes_w4a16(M, N, K):
+    G = K // 128
+    return N * K // 2 + 2 * N * G + 2 * M * K + 2 * M * N
+
+
+def alg_bytes_w4a4(M, N, K):
+    G = K // 128
+    return N * K // 2 + 2 * N * G + M * K // 2 + 4 * M * G + 2 * M * N
+
+
+def alg_bytes_quant(M, K):
+    return 2 * M * K + M * K // 2 + 4 * M * (K // 128)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=32, help="decoder blocks with distinct weights per step")
+    ap.add_argument("--config", type=int, default=2, help="workload configuration (2 = headline)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2410_11305_amd import binding as B
+    from paper_2410_11305_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    B.lib()
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    cfg = synth.CONFIGS[args.config]
+    Md, Mv = cfg.draft_M, cfg.verify_M
+    lins = list(cfg.layers)
+    L = args.layers
+    to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---- inputs: block 0 from the seeded NumPy recipe, further blocks drawn on
+    # the GPU with a seeded torch generator (same distributions), all packed by
+    # the library itself.
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(10000 * args.config + 99)
+    blobs = [[None] * len(lins) for _ in range(L)]
+    t_pack = 0.0
+    pack_bytes = 0
+    for i, lin in enumerate(lins):
+        N, K = lin.N, lin.K
+        for l in range(L):
+            if l == 0:
+                codes = to(synth.weight_codes(args.config, i, N, K))
+                scales = to(synth.weight_scales(args.config, i, N, K))
+            else:
+                codes = torch.randint(-8, 8, (N, K), dtype=torch.int8, device=dev, generator=gen)
+                scales = (torch.rand((N, K // 128), device=dev, generator=gen) * 0.008 + 0.002).half()
+            out = torch.empty(B.packed_weight_bytes(N, K), dtype=torch.uint8, device=dev)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            B.pack_weights(codes, scales, out)
+            e1.record()
+            e1.synchronize()
+            if l > 0:
+                t_pack += e0.elapsed_time(e1) * 1e-3
+                pack_bytes += N * K + 2 * N * (K // 128) + out.numel()
+            blobs[l][i] = out
+            del codes, scales
+    xd = [to(synth.activations(args.config, i, Md, lin.K, verify=False)) for i, lin in enumerate(lins)]
+    xv = [to(synth.activations(args.config, i, Mv, lin.K, verify=True)) for i, lin in enumerate(lins)]
+    qa = [torch.empty((Md, lin.K // 2), dtype=torch.uint8, device=dev) for lin in lins]
+    sa = [torch.empty((Md, lin.K // 128), dtype=torch.float32, device=dev) for lin in lins]
+    yd = [torch.empty((Md, lin.N), dtype=torch.float16, device=dev) for lin in lins]
+    yv = [torch.empty((Mv, lin.N), dtype=torch.float16, device=dev) for lin in lins]
+    ws_bytes = max([B.workspace_bytes(Md, l.N, l.K) for l in lins] + [B.workspace_bytes(Mv, l.N, l.K) for l in lins] + [16])
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    # ---- the passes
+    def run_quant():
+        for _ in range(L):
+            for i in range(len(lins)):
+                B.quant_act(xd[i], qa[i], sa[i])
+
+    def run_w4a4():
+        for l in range(L):
+            for i, lin in enumerate(lins):
+                B.gemm_w4a4(blobs[l][i], qa[i], sa[i], lin.N, y=yd[i], workspace=ws)
+
+    def run_draft():
+        for l in range(L):
+            for i, lin in enumerate(lins):
+                B.quant_act(xd[i], qa[i], sa[i])
+                B.gemm_w4a4(blobs[l][i], qa[i], sa[i], lin.N, y=yd[i], workspace=ws)
+
+    def run_verify():
+        for l in range(L):
+            for i, lin in enumerate(lins):
+                B.gemm_w4a16(blobs[l][i], xv[i], lin.N, y=yv[i], workspace=ws)
+
+    def run_w4a16_at_draft_M():
+        for l in range(L):
+            for i, lin in enumerate(lins):
+                B.gemm_w4a16(blobs[l][i], xd[i], lin.N, y=yd[i], workspace=ws)
+
+    def run_step():
+        run_draft()
+        run_verify()
+
+    def one_kind(fn_name, i):
+        lin = lins[i]
+
+        def f():
+            for l in range(L):
+                if fn_name == "w4a4":
+                    B.gemm_w4a4(blobs[l][i], qa[i], sa[i], lin.N, y=yd[i], workspace=ws)
+                else:
+                    B.gemm_w4a16(blobs[l][i], xv[i], lin.N, y=yv[i], workspace=ws)
+        return f
+
+    use_graph = not args.no_graph
+
+    def make_runner(fn):
+        """Returns a callable that enqueues fn's launches on the current stream
+        (replaying a captured HIP graph unless --no-graph)."""
+        fn()                       # eager once: first-call effects stay out of the capture
+        torch.cuda.synchronize()
+        if not use_graph:
+            return fn
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        torch.cuda.synchronize()
+        return g.replay
+
+    def time_runner(run, reps, warm):
+        for _ in range(warm):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps       # seconds per run
+
+    # ---- headline: K steps, wall clock bracketed by synchronize
+    step = make_runner(run_step)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / args.steps
+
+    bytes_draft = sum(alg_bytes_quant(Md, l.K) + alg_bytes_w4a4(Md, l.N, l.K) for l in lins) * L
+    bytes_verify = sum(alg_bytes_w4a16(Mv, l.N, l.K) for l in lins) * L
+    bytes_step = bytes_draft + bytes_verify
+    value = bytes_step / t_step / 1e12
+
+    # ---- per-kernel durations, HIP events on the launch stream
+    reps = max(3, min(20, args.steps // 5))
+    kernels = {}
+    t_q = time_runner(make_runner(run_quant), reps, 2)
+    kernels["quant_act"] = dict(launches=L * len(lins), seconds=t_q,
+                                bytes=sum(alg_bytes_quant(Md, l.K) for l in lins) * L, flops=0)
+    t_4 = time_runner(make_runner(run_w4a4), reps, 2)
+    kernels["gemm_w4a4"] = dict(launches=L * len(lins), seconds=t_4,
+                                bytes=sum(alg_bytes_w4a4(Md, l.N, l.K) for l in lins) * L,
+                                flops=sum(2 * Md * l.N * l.K for l in lins) * L)
+    t_16 = time_runner(make_runner(run_verify), reps, 2)
+    kernels["gemm_w4a16"] = dict(launches=L * len(lins), seconds=t_16, bytes=bytes_verify,
+                                 flops=sum(2 * Mv * l.N * l.K for l in lins) * L)
+    t_16d = time_runner(make_runner(run_w4a16_at_draft_M), reps, 2)
+    calls = {}
+    for i, lin in enumerate(lins):
+        for kind, M, ab in (("w4a4", Md, alg_bytes_w4a4), ("w4a16", Mv, alg_bytes_w4a16)):
+            t = time_runner(make_runner(one_kind(kind, i)), reps, 2) / L
+            calls[f"{lin.name}.{kind}.M{M}"] = dict(us=round(t * 1e6, 3),
+                                                    TBps=round(ab(M, lin.N, lin.K) / t / 1e12, 3))
+    dom = max(kernels, key=lambda k: kernels[k]["seconds"])
+    kd = kernels[dom]
+    achieved = kd["bytes"] / kd["seconds"] / 1e9
+    roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    avg_launch_us=round(kd["seconds"] / kd["launches"] * 1e6, 3),
+                    alg_bytes_per_launch=kd["bytes"] // kd["launches"])
+
+    # ---- CPU baseline: the oracle on one decoder block (bounded sample)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import qspec_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        host = []
+        for i, lin in enumerate(lins):
+            host.append((synth.weight_codes(args.config, i, lin.N, lin.K),
+                         synth.weight_scales(args.config, i, lin.N, lin.K),
+                         synth.activations(args.config, i, Md, lin.K, verify=False),
+                         synth.activations(args.config, i, Mv, lin.K, verify=True)))
+        c0 = time.perf_counter()
+        for codes, scales, hxd, hxv in host:
+            q, s = orc.quant_act(hxd)
+            orc.gemm_w4a4(q, s, codes, scales)
+            orc.gemm_w4a16(hxv, codes, scales)
+        c_t = time.perf_counter() - c0
+        cpu = dict(value=round(bytes_step / L / c_t / 1e12, 6), unit="TB/s", cores=int(cores), kind="oracle",
+                   sample=f"1 of {L} decoder blocks of the step (4 linears, draft M={Md} + verify M={Mv}), "
+                          f"{c_t:.1f} s of NumPy float64 oracle",
+                   seconds_per_block=round(c_t, 3))
+
+    out = {
+        "metric": "W4A4 & W4A16 GEMM us/call, achieved HBM TB/s + MFMA % at draft/verify M",
+        "value": round(value, 4),
+        "unit": "TB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(t_step * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int4 weights; int8 MFMA/int32 (draft), fp16 MFMA/fp32 (verify)",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config} ({cfg.label}): Llama-7B-shaped linears x {L} blocks, "
+                               f"draft W4A4 M={Md} (+quant_act), verify W4A16 M={Mv}",
+                   "layers": L, "launch": "hip-graph" if use_graph else "eager",
+                   "alg_bytes_per_step": bytes_step},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": {k: dict(avg_us=round(v["seconds"] / v["launches"] * 1e6, 3),
+                            GBps=round(v["bytes"] / v["seconds"] / 1e9, 1),
+                            TOPS=round(v["flops"] / v["seconds"] / 1e12, 2)) for k, v in kernels.items()},
+        "calls": calls,
+        "same_shape": {"w4a4_draft_pass_us": round((t_4 + t_q) * 1e6, 1),
+                       "w4a16_at_draft_M_pass_us": round(t_16d * 1e6, 1)},
+        "pack_weights_GBps": round(pack_bytes / t_pack / 1e9, 1) if t_pack > 0 else None,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
