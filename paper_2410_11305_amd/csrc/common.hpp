@@ -46,12 +46,14 @@ __device__ inline I8Pair unpack_i8(uint4 w) {
 // gives 1024 + 16u; (1024 + u) - 1032 and (1024 + 16u)/16 - 72 are both the
 // code, with no rounding.
 __device__ inline v8h dequant_word(uint32_t w) {
-  const uint32_t u = w ^ 0x88888888u;
-  const uint32_t u8 = u >> 8;
-  const uint32_t b0 = (u & 0x000F000Fu) | 0x64006400u;
-  const uint32_t b1 = (u & 0x00F000F0u) | 0x64006400u;
-  const uint32_t b2 = (u8 & 0x000F000Fu) | 0x64006400u;
-  const uint32_t b3 = (u8 & 0x00F000F0u) | 0x64006400u;
+  // (w & mask) ^ c is one three-input bit operation: the xor constant flips
+  // the nibble's sign bit (two's complement -> offset binary) and plants the
+  // 0x6400 exponent in the bits the mask cleared.
+  const uint32_t w8 = w >> 8;
+  const uint32_t b0 = (w & 0x000F000Fu) ^ 0x64086408u;
+  const uint32_t b1 = (w & 0x00F000F0u) ^ 0x64806480u;
+  const uint32_t b2 = (w8 & 0x000F000Fu) ^ 0x64086408u;
+  const uint32_t b3 = (w8 & 0x00F000F0u) ^ 0x64806480u;
   const v2h k1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
   const v2h k72 = {(_Float16)72.0f, (_Float16)72.0f};
   const v2h k16th = {(_Float16)0.0625f, (_Float16)0.0625f};

@@ -4,10 +4,13 @@
 #include "qspec.h"
 
 #include <hip/hip_runtime.h>
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "common.hpp"
 #include "gemm_generic.hpp"
+#include "gemm_small.hpp"
 #include "pack.hpp"
 #include "quant_act.hpp"
 
@@ -63,6 +66,109 @@ void launch_w4a16(const GemmArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((gemm_w4a16_generic<TM, 4>), grid, dim3(256), 0, s, a);
 }
 
+
+// ---------------------------------------------------------------- small-M plans
+// A plan fixes the workgroup shape (WN x WK wavefronts), the number of
+// K-chunks S and the LDS footprint.  It is a pure function of (mode, M, N, K),
+// so qspec_workspace_bytes and the GEMM entry points always agree.
+struct SmallPlan {
+  bool use;        // false: fall back to the generic kernel
+  int TM, WN, WK, S, gc_max;
+  size_t lds_bytes;
+};
+
+constexpr int kLdsCap = 64 * 1024;
+constexpr int kSmallMaxM = 32;
+
+// QSPEC_PLAN_W4A4 / QSPEC_PLAN_W4A16 = "WN,WK,S" override the heuristic
+// (benchmark A/B only; a plan that does not fit is ignored).
+bool plan_override(bool w4a4, int* wn, int* wk, int* s) {
+  const char* e = getenv(w4a4 ? "QSPEC_PLAN_W4A4" : "QSPEC_PLAN_W4A16");
+  if (!e) return false;
+  return sscanf(e, "%d,%d,%d", wn, wk, s) == 3;
+}
+
+// One staging pass must cover a chunk: kStageU 16-byte pieces per thread and
+// row, one 8-byte scale piece per thread, two activation scales per thread.
+template <bool W4A4>
+bool small_stage_fits(int TM, int WN, int gc_max) {
+  const int tpr = 512 / (TM * 16);
+  if (gc_max * (W4A4 ? 4 : 16) > tpr * kStageU) return false;
+  if (gc_max * WN * 4 > 512) return false;
+  if (W4A4 && gc_max * TM * 16 > 1024) return false;
+  return true;
+}
+
+template <bool W4A4>
+size_t small_lds_bytes(int TM, int WN, int WK, int gc_max) {
+  if (!small_stage_fits<W4A4>(TM, WN, gc_max)) return (size_t)1 << 30;
+  size_t total = TM == 1 ? (size_t)SmallLds<W4A4, 1>(gc_max, WN).total : (size_t)SmallLds<W4A4, 2>(gc_max, WN).total;
+  const size_t red = WK > 1 ? (size_t)WK * WN * TM * 4 * 64 * 4 : 0;
+  return total > red ? total : red;
+}
+
+template <bool W4A4>
+SmallPlan plan_small(int M, int N, int K) {
+  SmallPlan p{};
+  const int G = K / kGroup;
+  if (M > kSmallMaxM) return p;
+  p.TM = M <= 16 ? 1 : 2;
+  int wn = W4A4 ? 1 : 8, wk = W4A4 ? 8 : 1, s = 0;
+  const bool forced = plan_override(W4A4, &wn, &wk, &s);
+  const bool shape_ok = (wn == 1 || wn == 2 || wn == 4 || wn == 8) && wn * wk == 8;
+  if (!shape_ok) { wn = W4A4 ? 1 : 8; wk = 8 / wn; s = 0; }
+  p.WN = wn; p.WK = wk;
+  const int NB = (N / 16 + wn - 1) / wn;
+  // smallest S whose chunk fits the LDS cap
+  int s_min = 1;
+  while (s_min < G && small_lds_bytes<W4A4>(p.TM, wn, wk, (G + s_min - 1) / s_min) > (size_t)kLdsCap) ++s_min;
+  if (small_lds_bytes<W4A4>(p.TM, wn, wk, (G + s_min - 1) / s_min) > (size_t)kLdsCap) return p;
+  if (!(forced && s >= s_min && s <= G)) {
+    const int target = 512;                 // about two workgroups per CU
+    s = (target + NB / 2) / NB;
+    if (s < s_min) s = s_min;
+    if (s > G) s = G;
+    if (W4A4 && s_min == 1 && NB >= 256) s = 1;
+  }
+  p.S = s;
+  p.gc_max = (G + s - 1) / s;
+  p.lds_bytes = small_lds_bytes<W4A4>(p.TM, wn, wk, p.gc_max);
+  p.use = true;
+  return p;
+}
+
+template <bool W4A4, int TM, int WN, int WK>
+void launch_small_inst(const SmallArgs& a, size_t lds, hipStream_t s) {
+  dim3 grid((a.N / 16 + WN - 1) / WN, a.S);
+  hipLaunchKernelGGL((gemm_small_kernel<W4A4, TM, WN, WK, 8>), grid, dim3(WN * WK * 64), lds, s, a);
+}
+
+template <bool W4A4, int TM>
+void launch_small_tm(const SmallPlan& p, const SmallArgs& a, hipStream_t s) {
+  switch (p.WN) {
+    case 1: launch_small_inst<W4A4, TM, 1, 8>(a, p.lds_bytes, s); break;
+    case 2: launch_small_inst<W4A4, TM, 2, 4>(a, p.lds_bytes, s); break;
+    case 4: launch_small_inst<W4A4, TM, 4, 2>(a, p.lds_bytes, s); break;
+    default: launch_small_inst<W4A4, TM, 8, 1>(a, p.lds_bytes, s); break;
+  }
+}
+
+template <bool W4A4>
+void launch_small(const SmallPlan& p, SmallArgs a, hipStream_t s) {
+  a.S = p.S;
+  a.gc_max = p.gc_max;
+  if (p.TM == 1) launch_small_tm<W4A4, 1>(p, a, s); else launch_small_tm<W4A4, 2>(p, a, s);
+  if (p.S > 1) {
+    const size_t n_quads = (size_t)a.M * a.N / 4;
+    hipLaunchKernelGGL(splitk_finish_kernel, dim3(blocks_for(n_quads, 256)), dim3(256), 0, s,
+                       reinterpret_cast<const float4*>(a.ws), reinterpret_cast<uint2*>(a.y), n_quads, p.S);
+  }
+}
+
+inline size_t plan_ws_bytes(const SmallPlan& p, int M, int N) {
+  return p.use && p.S > 1 ? (size_t)p.S * M * N * 4 : 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -89,7 +195,9 @@ size_t qspec_packed_weight_bytes(int N, int K, int group) {
 
 size_t qspec_workspace_bytes(int M, int N, int K, int group) {
   if (check_shape(M, N, K, group) != QSPEC_OK) return 0;
-  return 0;   // every current kernel combines its K-splits inside the workgroup
+  const size_t a = plan_ws_bytes(plan_small<true>(M, N, K), M, N);
+  const size_t b = plan_ws_bytes(plan_small<false>(M, N, K), M, N);
+  return a > b ? a : b;
 }
 
 int qspec_pack_weights(const int8_t* codes, const void* scales_f16, int N, int K, int group,
@@ -154,6 +262,15 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int 
   a.y = static_cast<uint16_t*>(y_f16);
   a.M = M; a.N = N; a.K = K; a.G = K / kGroup;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  const SmallPlan plan = plan_small<true>(M, N, K);
+  if (plan.use) {
+    SmallArgs sa_{};
+    sa_.codes = a.codes; sa_.scalesT = a.scalesT; sa_.act = qa; sa_.sa = sa; sa_.y = a.y;
+    sa_.ws = static_cast<float*>(workspace);
+    sa_.M = M; sa_.N = N; sa_.K = K; sa_.G = a.G;
+    launch_small<true>(plan, sa_, s);
+    return launch_status();
+  }
   switch (pick_tm(M)) {
     case 1: launch_w4a4<1>(a, s); break;
     case 2: launch_w4a4<2>(a, s); break;
@@ -178,6 +295,15 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16, int M, int N, int K,
   a.y = static_cast<uint16_t*>(y_f16);
   a.M = M; a.N = N; a.K = K; a.G = K / kGroup;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  const SmallPlan plan = plan_small<false>(M, N, K);
+  if (plan.use) {
+    SmallArgs sa_{};
+    sa_.codes = a.codes; sa_.scalesT = a.scalesT; sa_.act = x_f16; sa_.y = a.y;
+    sa_.ws = static_cast<float*>(workspace);
+    sa_.M = M; sa_.N = N; sa_.K = K; sa_.G = a.G;
+    launch_small<false>(plan, sa_, s);
+    return launch_status();
+  }
   switch (pick_tm(M)) {
     case 1: launch_w4a16<1>(a, s); break;
     case 2: launch_w4a16<2>(a, s); break;
