@@ -241,16 +241,23 @@ def main() -> int:
                          synth.weight_scales(args.config, i, lin.N, lin.K),
                          synth.activations(args.config, i, Md, lin.K, verify=False),
                          synth.activations(args.config, i, Mv, lin.K, verify=True)))
+        # one decoder block is the unit; repeat it until about 10 s of oracle time
         c0 = time.perf_counter()
-        for codes, scales, hxd, hxv in host:
-            q, s = orc.quant_act(hxd)
-            orc.gemm_w4a4(q, s, codes, scales)
-            orc.gemm_w4a16(hxv, codes, scales)
-        c_t = time.perf_counter() - c0
-        cpu = dict(value=round(bytes_step / L / c_t / 1e12, 6), unit="TB/s", cores=int(cores), kind="oracle",
-                   sample=f"1 of {L} decoder blocks of the step (4 linears, draft M={Md} + verify M={Mv}), "
-                          f"{c_t:.1f} s of NumPy float64 oracle",
-                   seconds_per_block=round(c_t, 3))
+        n_rep = 0
+        while True:
+            for codes, scales, hxd, hxv in host:
+                q, s = orc.quant_act(hxd)
+                orc.gemm_w4a4(q, s, codes, scales)
+                orc.gemm_w4a16(hxv, codes, scales)
+            n_rep += 1
+            c_t = time.perf_counter() - c0
+            if c_t >= 10.0 or n_rep >= L:
+                break
+        cpu = dict(value=round(bytes_step / L * n_rep / c_t / 1e12, 6), unit="TB/s", cores=int(cores),
+                   kind="oracle",
+                   sample=f"{n_rep} of the {L} decoder blocks of one step (4 linears each, draft M={Md} + "
+                          f"verify M={Mv}), {c_t:.1f} s of NumPy float64 oracle",
+                   seconds_per_block=round(c_t / n_rep, 3))
 
     out = {
         "metric": "W4A4 & W4A16 GEMM us/call, achieved HBM TB/s + MFMA % at draft/verify M",

@@ -28,17 +28,18 @@
  * Packed weight blob (written by qspec_pack_weights, N*K/2 + N*G*2 bytes)
  *   codes  : tiles of 16 output rows x 128 input features (one group), 1024
  *            bytes each, tile (T = n/16, g = k/128) at byte (T*G + g)*1024.
- *            Inside a tile the 16 bytes at offset 16*(16*kb + n%16) hold the
- *            32 codes k%128 in [32*kb, 32*kb+32) of row n as four 32-bit
- *            little-endian words, word i = codes 8i..8i+7 of those 32.  In a
+ *            Inside a tile the 16 bytes at offset 16*(16*kb + n%16), kb = 0..3,
+ *            are four 32-bit little-endian words of row n; word i (i = 0..3)
+ *            holds the 8 codes k%128 in [32*i + 8*kb, 32*i + 8*kb + 8).  In a
  *            word the eight 4-bit two's-complement codes c0..c7 sit at bit
  *            positions 4*p with p = 0..7 holding c0,c2,c4,c6,c1,c3,c5,c7.
  *   scales : fp16, transposed to [G][N], starting at byte N*K/2.
  *
  * Quantised activations (written by qspec_quant_act)
- *   qa : M rows of K/2 bytes; each aligned run of 8 codes is one 32-bit word
- *        with the same nibble order as a weight word (c0,c2,c4,c6,c1,c3,c5,c7
- *        from bit 0 upward).
+ *   qa : M rows of K/2 bytes, 64 bytes per group.  Each aligned run of 8
+ *        codes is one 32-bit word with the nibble order of a weight word
+ *        (c0,c2,c4,c6,c1,c3,c5,c7 from bit 0 upward); inside a group the word
+ *        of codes [32*i + 8*kb, +8) is stored at word position 4*kb + i.
  *   sa : fp32 [M][G], row-major.
  */
 #ifndef QSPEC_H

@@ -12,10 +12,12 @@ Layout specification
            32-bit word; 4-bit two's-complement code c_e sits at bit 4*POS[e]
            with POS = (0, 4, 1, 5, 2, 6, 3, 7).
   weights: tiles of 16 rows x 128 k (1024 B); tile (T, g) at byte
-           (T*G + g)*1024; inside, the 16 bytes at 16*(16*kb + r) are the four
-           words of row 16T + r covering k%128 in [32kb, 32kb + 32).
+           (T*G + g)*1024; inside, the 16 bytes at 16*(16*kb + r), kb = 0..3,
+           are four words of row 16T + r: word i covers k%128 in
+           [32i + 8kb, 32i + 8kb + 8).
            After all tiles: fp16 scales transposed to [G][N].
-  acts   : row-major, word w of row m at byte m*K/2 + 4w.
+  acts   : row-major, 16 words per group; the word of codes k%128 in
+           [32i + 8kb, +8) sits at word position 4kb + i of its group.
 """
 from __future__ import annotations
 
@@ -47,15 +49,27 @@ def _codes_from_words(words: np.ndarray) -> np.ndarray:
     return out.reshape(R, W * 8).astype(np.int8)
 
 
+def pack_words(codes: np.ndarray) -> np.ndarray:
+    """Public form of the word packer: int8 [R, K] -> uint32 [R, K/8]."""
+    return _words(np.asarray(codes))
+
+
 def act_bytes(codes: np.ndarray) -> np.ndarray:
     """int8 codes [M, K] -> uint8 [M, K/2] as the activation quantiser stores them."""
-    words = _words(np.asarray(codes))
-    return words.astype("<u4").view(np.uint8).reshape(codes.shape[0], -1)
+    codes = np.asarray(codes)
+    M, K = codes.shape
+    if K % GROUP:
+        raise ValueError("K must be a multiple of 128")
+    words = _words(codes).reshape(M, K // GROUP, 4, 4)          # [m, g, i, kb]  (k-word = 4i + kb)
+    words = np.ascontiguousarray(words.transpose(0, 1, 3, 2))   # stored at position 4kb + i
+    return words.astype("<u4").view(np.uint8).reshape(M, -1)
 
 
 def decode_act_bytes(qa: np.ndarray) -> np.ndarray:
     qa = np.ascontiguousarray(qa, dtype=np.uint8)
-    words = qa.view("<u4")
+    M = qa.shape[0]
+    words = qa.view("<u4").reshape(M, -1, 4, 4)                 # [m, g, kb, i]
+    words = np.ascontiguousarray(words.transpose(0, 1, 3, 2)).reshape(M, -1)
     return _codes_from_words(words)
 
 
@@ -70,9 +84,9 @@ def weight_blob(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
     if scales.shape != (N, G) or scales.dtype != np.float16:
         raise ValueError("scales must be fp16 [N, G]")
     words = _words(codes)                                   # [N, K/8]
-    # n = 16T + r ; word index = 16g + 4kb + i
-    w5 = words.reshape(N // 16, 16, G, 4, 4)                # [T, r, g, kb, i]
-    tiles = np.ascontiguousarray(w5.transpose(0, 2, 3, 1, 4))   # [T, g, kb, r, i]
+    # n = 16T + r ; k-word index inside the row = 16g + 4i + kb
+    w5 = words.reshape(N // 16, 16, G, 4, 4)                # [T, r, g, i, kb]
+    tiles = np.ascontiguousarray(w5.transpose(0, 2, 4, 1, 3))   # [T, g, kb, r, i]
     code_bytes = tiles.astype("<u4").view(np.uint8).reshape(-1)
     scale_bytes = np.ascontiguousarray(scales.T).view(np.uint8).reshape(-1)
     return np.concatenate([code_bytes, scale_bytes])
@@ -84,7 +98,7 @@ def decode_weight_blob(blob: np.ndarray, N: int, K: int):
     blob = np.ascontiguousarray(blob, dtype=np.uint8)
     nb = N * K // 2
     tiles = blob[:nb].view("<u4").reshape(N // 16, G, 4, 16, 4)     # [T, g, kb, r, i]
-    words = np.ascontiguousarray(tiles.transpose(0, 3, 1, 2, 4)).reshape(N, K // 8)
+    words = np.ascontiguousarray(tiles.transpose(0, 3, 1, 4, 2)).reshape(N, K // 8)   # [T, r, g, i, kb]
     scales = blob[nb:nb + 2 * N * G].view(np.float16).reshape(G, N).T
     return _codes_from_words(words), np.ascontiguousarray(scales)
 
@@ -94,8 +108,8 @@ def weight_byte_offset(n: int, k: int, G: int) -> int:
     used by the pin that walks the blob code by code)."""
     T, r = divmod(n, 16)
     g, kk = divmod(k, GROUP)
-    kb, k32 = divmod(kk, 32)
-    i, e = divmod(k32, 8)
+    i, k32 = divmod(kk, 32)
+    kb, e = divmod(k32, 8)
     return (T * G + g) * 1024 + 16 * (16 * kb + r) + 4 * i + POS[e] // 2
 
 

@@ -157,11 +157,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_w4a16_generic(GemmArgs p) {
       const int m = m0 + 16 * t + r16;
       const bool valid = m < p.M;
       const int mc = valid ? m : p.M - 1;
-      const uint16_t* xr = x + (size_t)mc * p.K + g * kGroup + kb * 32;
+      const uint16_t* xr = x + (size_t)mc * p.K + g * kGroup + kb * 8;
       v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        uint4 xq = *reinterpret_cast<const uint4*>(xr + 8 * i);
+        uint4 xq = *reinterpret_cast<const uint4*>(xr + 32 * i);
         if (!valid) xq = uint4{0u, 0u, 0u, 0u};
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[i], __builtin_bit_cast(v8h, xq), acc, 0, 0, 0);
       }

@@ -182,11 +182,11 @@ __global__ __launch_bounds__(WN * WK * 64) void gemm_small_kernel(SmallArgs p) {
             wa[3] = dequant_word(wq.w);
 #pragma unroll
             for (int t = 0; t < TM; ++t) {
-              const uint8_t* xr = lds + (16 * t + r16) * L.act_pitch + gl * 256 + kb * 64;
+              const uint8_t* xr = lds + (16 * t + r16) * L.act_pitch + gl * 256 + kb * 16;
               v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
-                const uint4 xq = *reinterpret_cast<const uint4*>(xr + 16 * i);
+                const uint4 xq = *reinterpret_cast<const uint4*>(xr + 64 * i);
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[i], __builtin_bit_cast(v8h, xq), acc, 0, 0, 0);
               }
 #pragma unroll

@@ -1,0 +1,267 @@
+// Memory-bound (small M) kernels for both modes, wave-autonomous form.
+//
+// A workgroup of 8 wavefronts owns NT adjacent weight tiles (16 outputs each)
+// over the whole of K.  Wave w takes the K groups g = w, w+8, w+16, ...; for
+// each of them it loads the activation operand of that group ONCE into
+// registers (straight from global memory: the activations are small and stay
+// in L2) and re-uses it against the NT weight tiles, which stream from HBM
+// exactly once.  Nothing is staged in LDS, so there is no barrier in the
+// streaming loop and no split-K pass over a workspace: the eight per-wave
+// fp32 sums of a tile are combined through LDS at the very end and stored as
+// fp16.
+//
+// All global loads are unconditional buffer loads (work that does not exist
+// gets an out-of-range offset, which reads as zero without memory traffic;
+// a load inside a branch would make the compiler drain the whole memory
+// pipeline at every use) and two register sets alternate, so that the loads
+// of the next group are in flight while the current one is computed.
+//
+// MFMA operand roles: A = weights (row = n % 16), B = activations (column =
+// m % 16), k-block = lane / 16; D[i][j]: lane holds rows 4*(lane/16)+r.
+#pragma once
+#include "common.hpp"
+
+namespace qspec {
+
+struct StreamArgs {
+  const uint4* codes;        // blob code tiles
+  const uint16_t* scalesT;   // blob fp16 scales [G][N]
+  const void* act;           // W4A4: qa bytes [M][K/2]; W4A16: x fp16 [M][K]
+  const float* sa;           // W4A4: [M][G]
+  uint16_t* y;               // fp16 [M][N]
+  int M, N, K, G;
+};
+
+constexpr int kStreamWaves = 8;
+
+// Buffer descriptors: a raw buffer load whose byte offset lies outside the
+// buffer returns zero WITHOUT touching memory.  Every load below is therefore
+// unconditional; work that does not exist (a group past K, a token row past
+// M) is expressed as an out-of-range offset instead of a branch.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr uint32_t kOutOfRange = 0x80000000u;     // beyond any buffer this library accepts (< 2 GiB)
+
+__device__ inline rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+__device__ inline uint4 buf_load16(rsrc_t r, uint32_t off) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+  return uint4{v.x, v.y, v.z, v.w};
+}
+// streaming variant (weights are read once: do not keep them in the caches)
+__device__ inline uint4 buf_load16_stream(rsrc_t r, uint32_t off) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 2);
+  return uint4{v.x, v.y, v.z, v.w};
+}
+__device__ inline uint2 buf_load8(rsrc_t r, uint32_t off) {
+  typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+  return uint2{v.x, v.y};
+}
+__device__ inline float buf_load_f32(rsrc_t r, uint32_t off) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
+}
+
+struct StreamRsrc {
+  rsrc_t codes, scales, act, sa;
+};
+
+template <bool W4A4, int TM, int NT>
+struct GroupRegs {
+  uint4 w[NT];                      // one weight tile slice per n-tile
+  uint2 sw[NT];                     // 4 fp16 weight scales (rows 4*kb .. 4*kb+3 of the tile)
+  uint4 a[W4A4 ? TM : TM * 4];      // activation operand(s) of this group
+  float sa[W4A4 ? TM : 1];          // activation scales (W4A4)
+};
+
+// Issue every load of group g (valid == false: all offsets out of range, no traffic).
+template <bool W4A4, int TM, int NT>
+__device__ inline void load_group(GroupRegs<W4A4, TM, NT>& R, const StreamRsrc& rs, const StreamArgs& p, int g,
+                                  bool valid, int T0, int nt_valid, int lane) {
+  const int r16 = lane & 15, kb = lane >> 4;
+  // activations first: loads return in order, and the (L2-resident) activations
+  // must not queue behind the HBM weight tiles
+#pragma unroll
+  for (int t = 0; t < TM; ++t) {
+    const uint32_t m = 16 * t + r16;               // rows past M lie past the end of the buffer: they read as 0
+    if (W4A4) {
+      R.a[t] = buf_load16(rs.act, valid ? m * (uint32_t)(p.K / 2) + 64u * g + 16u * kb : kOutOfRange);
+      R.sa[t] = buf_load_f32(rs.sa, valid ? (m * p.G + g) * 4u : kOutOfRange);
+    } else {
+      // Coalesced form: load u = 4t + i covers token rows 4u .. 4u+3, 256 contiguous
+      // bytes (one group) per row, 16 lanes per row.  compute_group turns this into
+      // the MFMA operand layout through a wave-private LDS buffer.  (Loading the
+      // operand layout directly touches 16 rows x 64 bytes at a 2K-byte stride per
+      // instruction, which the caches serve at a fraction of their bandwidth.)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t row = 4u * (4 * t + i) + kb;
+        R.a[t * 4 + i] = buf_load16(rs.act, valid ? (row * (uint32_t)p.K + (uint32_t)g * kGroup) * 2u + r16 * 16u
+                                                  : kOutOfRange);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const bool ok = valid && j < nt_valid;
+    const uint32_t T = (uint32_t)(T0 + j);
+    R.w[j] = buf_load16_stream(rs.codes, ok ? (T * p.G + g) * 1024u + lane * 16u : kOutOfRange);
+    R.sw[j] = buf_load8(rs.scales, ok ? ((uint32_t)g * p.N + T * 16u + 4u * kb) * 2u : kOutOfRange);
+  }
+}
+
+constexpr int kXPitch = 256 + 16;     // bytes per token row of the transpose buffer (odd number of 16-byte slots)
+
+template <bool W4A4, int TM, int NT>
+__device__ inline void compute_group(const GroupRegs<W4A4, TM, NT>& R, float (&facc)[NT][TM][4], uint8_t* xbuf,
+                                     int lane) {
+  if (W4A4) {
+    I8Pair b[TM];
+#pragma unroll
+    for (int t = 0; t < TM; ++t) b[t] = unpack_i8(R.a[t]);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const I8Pair a = unpack_i8(R.w[j]);
+      float sw[4];
+      // both int8 operands carry a factor 16: fold 2^-8 into the weight scale (exact)
+      sw[0] = half_bits_to_float((uint16_t)(R.sw[j].x & 0xFFFF)) * 0.00390625f;
+      sw[1] = half_bits_to_float((uint16_t)(R.sw[j].x >> 16)) * 0.00390625f;
+      sw[2] = half_bits_to_float((uint16_t)(R.sw[j].y & 0xFFFF)) * 0.00390625f;
+      sw[3] = half_bits_to_float((uint16_t)(R.sw[j].y >> 16)) * 0.00390625f;
+#pragma unroll
+      for (int t = 0; t < TM; ++t) {
+        v4i acc = {0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a.lo, b[t].lo, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a.hi, b[t].hi, acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) facc[j][t][r] += (float)acc[r] * (R.sa[t] * sw[r]);
+      }
+    }
+  } else {
+    // rows x 256 B (as loaded) -> operand layout: lane (r16, kb), step i reads the
+    // 16 bytes of row 16t + r16 that hold k = 32i + 8kb .. +8.  Only this wave
+    // touches xbuf and LDS executes a wave's accesses in order: no barrier.
+    const int r16 = lane & 15, kb = lane >> 4;
+#pragma unroll
+    for (int u = 0; u < TM * 4; ++u)
+      *reinterpret_cast<uint4*>(xbuf + (4 * u + kb) * kXPitch + r16 * 16) = R.a[u];
+    uint4 xb[TM * 4];
+#pragma unroll
+    for (int t = 0; t < TM; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        xb[t * 4 + i] = *reinterpret_cast<const uint4*>(xbuf + (16 * t + r16) * kXPitch + (4 * i + kb) * 16);
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      v8h wa[4];
+      wa[0] = dequant_word(R.w[j].x);
+      wa[1] = dequant_word(R.w[j].y);
+      wa[2] = dequant_word(R.w[j].z);
+      wa[3] = dequant_word(R.w[j].w);
+      float sw[4];
+      sw[0] = half_bits_to_float((uint16_t)(R.sw[j].x & 0xFFFF));
+      sw[1] = half_bits_to_float((uint16_t)(R.sw[j].x >> 16));
+      sw[2] = half_bits_to_float((uint16_t)(R.sw[j].y & 0xFFFF));
+      sw[3] = half_bits_to_float((uint16_t)(R.sw[j].y >> 16));
+#pragma unroll
+      for (int t = 0; t < TM; ++t) {
+        v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(wa[i], __builtin_bit_cast(v8h, xb[t * 4 + i]), acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) facc[j][t][r] += acc[r] * sw[r];
+      }
+    }
+  }
+}
+
+template <bool W4A4, int TM, int NT>
+__global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamArgs p) {
+  constexpr int W = kStreamWaves;
+  // LDS: per-wave transpose buffers while streaming (verify mode), re-used as the
+  // split-K reduction buffer at the end
+  constexpr int kRedBytes = W * NT * TM * 4 * kWave * 4;
+  constexpr int kXBytes = W4A4 ? 0 : W * TM * 16 * kXPitch;
+  __shared__ __attribute__((aligned(16))) uint8_t lds[kRedBytes > kXBytes ? kRedBytes : kXBytes];
+  float (*red)[NT * TM * 4][kWave] = reinterpret_cast<float (*)[NT * TM * 4][kWave]>(lds);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r16 = lane & 15, kb = lane >> 4;
+  const int T0 = blockIdx.x * NT;
+  const int nt_valid = min(NT, p.N / 16 - T0);        // >= 1 by construction of the grid
+  const int G = p.G;
+  // groups of this wave: wave, wave + W, ...  (n_g of them, possibly none)
+  const int n_g = (G - wave + W - 1) / W;
+
+  float facc[NT][TM][4];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int t = 0; t < TM; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) facc[j][t][r] = 0.0f;
+
+  uint8_t* xbuf = lds + (W4A4 ? 0 : wave * TM * 16 * kXPitch);
+  if (n_g > 0) {
+    StreamRsrc rs;
+    rs.codes = make_rsrc(p.codes, (uint32_t)((size_t)p.N * p.K / 2));
+    rs.scales = make_rsrc(p.scalesT, (uint32_t)((size_t)p.N * G * 2));
+    rs.act = make_rsrc(p.act, (uint32_t)(W4A4 ? (size_t)p.M * p.K / 2 : (size_t)p.M * p.K * 2));
+    rs.sa = make_rsrc(W4A4 ? (const void*)p.sa : p.act, (uint32_t)((size_t)p.M * G * 4));
+    // Workgroups start at different points of their K sequence so that the 256
+    // CUs do not all ask L2 for the same activation lines at the same moment.
+    const int rot = (int)(blockIdx.x % (unsigned)n_g);
+    auto grp = [&](int it) { int q = it + rot; q = q >= n_g ? q - n_g : q; return wave + q * W; };
+    // Two register sets alternate: the loads of the next group are in flight
+    // while one group is computed.  (A third set was measured and is slower: the
+    // memory system is throughput-bound here, more requests in flight only
+    // queue up.)  The scheduling barriers pin the order "issue loads, then
+    // compute": without them the compiler sinks the loads below the arithmetic.
+    GroupRegs<W4A4, TM, NT> A, B;
+    load_group<W4A4, TM, NT>(A, rs, p, grp(0), true, T0, nt_valid, lane);
+    for (int it = 0; it < n_g; it += 2) {
+      load_group<W4A4, TM, NT>(B, rs, p, grp(it + 1), it + 1 < n_g, T0, nt_valid, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      compute_group<W4A4, TM, NT>(A, facc, xbuf, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      load_group<W4A4, TM, NT>(A, rs, p, grp(it + 2), it + 2 < n_g, T0, nt_valid, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      if (it + 1 < n_g) compute_group<W4A4, TM, NT>(B, facc, xbuf, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // ---- combine the eight K-slices of every output tile
+  __syncthreads();               // the transpose buffers are dead from here on
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int t = 0; t < TM; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[wave][(j * TM + t) * 4 + r][lane] = facc[j][t][r];
+  __syncthreads();
+  for (int o = wave; o < NT * TM; o += W) {
+    const int j = o / TM, t = o - j * TM;
+    float s[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float v = 0.0f;
+#pragma unroll
+      for (int w = 0; w < W; ++w) v += red[w][o * 4 + r][lane];
+      s[r] = v;
+    }
+    const int m = 16 * t + r16;
+    if (j < nt_valid && m < p.M) {
+      uint2 out;
+      out.x = (uint32_t)float_to_half_bits(s[0]) | ((uint32_t)float_to_half_bits(s[1]) << 16);
+      out.y = (uint32_t)float_to_half_bits(s[2]) | ((uint32_t)float_to_half_bits(s[3]) << 16);
+      *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + (T0 + j) * 16 + 4 * kb) = out;
+    }
+  }
+}
+
+}  // namespace qspec

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void pack_codes_kernel(const int8_t* __restric
   const int g = (int)(tile % G);
   const int T = (int)(tile / G);
   const int n = T * kTileRows + (lane & 15);
-  const int k0 = g * kGroup + (lane >> 4) * 32 + i * 8;
+  const int k0 = g * kGroup + i * 32 + (lane >> 4) * 8;   // word i of k-block kb covers 32i + 8kb ..
   const uint2 raw = *reinterpret_cast<const uint2*>(codes + (size_t)n * K + k0);
   uint32_t w = 0;
 #pragma unroll
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(const uint32_t* __res
   const int g = (int)(tile % G);
   const int T = (int)(tile / G);
   const int n = T * kTileRows + (lane & 15);
-  const int k0 = g * kGroup + (lane >> 4) * 32 + i * 8;
+  const int k0 = g * kGroup + i * 32 + (lane >> 4) * 8;   // word i of k-block kb covers 32i + 8kb ..
   const uint32_t w = blob_words[o];
   uint2 raw = {0u, 0u};
 #pragma unroll

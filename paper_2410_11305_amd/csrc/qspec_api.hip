@@ -11,6 +11,7 @@
 #include "common.hpp"
 #include "gemm_generic.hpp"
 #include "gemm_small.hpp"
+#include "gemm_stream.hpp"
 #include "pack.hpp"
 #include "quant_act.hpp"
 
@@ -25,8 +26,9 @@ inline int check_shape(int M, int N, int K, int group) {
   if (K <= 0 || K % kGroup != 0) return QSPEC_ERR_SHAPE;
   if (N <= 0 || N % kTileRows != 0) return QSPEC_ERR_SHAPE;
   if (M < 1) return QSPEC_ERR_SHAPE;
-  // 32-bit tile / row indices are used inside the kernels
-  if ((long long)N * (K / kGroup) > 0x7fffffffLL) return QSPEC_ERR_SHAPE;
+  // 32-bit byte offsets are used inside the kernels: every buffer stays below 2 GiB
+  if ((long long)N * K / 2 >= 0x7fffffffLL) return QSPEC_ERR_SHAPE;
+  if ((long long)M * K * 2 >= 0x7fffffffLL) return QSPEC_ERR_SHAPE;
   return QSPEC_OK;
 }
 
@@ -165,6 +167,53 @@ void launch_small(const SmallPlan& p, SmallArgs a, hipStream_t s) {
   }
 }
 
+
+// ---------------------------------------------------------------- streaming (small-M) kernel
+constexpr int kStreamMaxM = 32;
+constexpr int kNumCU = 256;
+
+// n-tiles per workgroup: minimise rounds x work per round over the 256 CUs, prefer
+// the larger NT on a tie (the activation operand is re-used NT times).
+// QSPEC_STREAM_NT=1..4 overrides (benchmark A/B only).
+int stream_nt(int N) {
+  const int tiles = N / 16;
+  if (const char* e = getenv("QSPEC_STREAM_NT")) {
+    const int v = atoi(e);
+    if (v >= 1 && v <= 4) return v;
+  }
+  int best = 1, best_cost = 1 << 30;
+  for (int nt = 1; nt <= 4; ++nt) {
+    const int blocks = (tiles + nt - 1) / nt;
+    const int cost = ((blocks + kNumCU - 1) / kNumCU) * nt;
+    if (cost <= best_cost) { best_cost = cost; best = nt; }
+  }
+  return best;
+}
+
+bool use_stream(int M) {
+  if (M > kStreamMaxM) return false;
+  const char* e = getenv("QSPEC_KERNEL");
+  return !(e && strcmp(e, "small") == 0);
+}
+
+template <bool W4A4, int TM>
+void launch_stream_tm(const StreamArgs& a, int nt, hipStream_t s) {
+  const int tiles = a.N / 16;
+  dim3 grid((tiles + nt - 1) / nt), block(kStreamWaves * 64);
+  switch (nt) {
+    case 1: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 1>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 2>), grid, block, 0, s, a); break;
+    case 3: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 3>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 4>), grid, block, 0, s, a); break;
+  }
+}
+
+template <bool W4A4>
+void launch_stream(const StreamArgs& a, hipStream_t s) {
+  const int nt = stream_nt(a.N);
+  if (a.M <= 16) launch_stream_tm<W4A4, 1>(a, nt, s); else launch_stream_tm<W4A4, 2>(a, nt, s);
+}
+
 inline size_t plan_ws_bytes(const SmallPlan& p, int M, int N) {
   return p.use && p.S > 1 ? (size_t)p.S * M * N * 4 : 0;
 }
@@ -195,6 +244,7 @@ size_t qspec_packed_weight_bytes(int N, int K, int group) {
 
 size_t qspec_workspace_bytes(int M, int N, int K, int group) {
   if (check_shape(M, N, K, group) != QSPEC_OK) return 0;
+  if (use_stream(M)) return 0;
   const size_t a = plan_ws_bytes(plan_small<true>(M, N, K), M, N);
   const size_t b = plan_ws_bytes(plan_small<false>(M, N, K), M, N);
   return a > b ? a : b;
@@ -262,6 +312,13 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int 
   a.y = static_cast<uint16_t*>(y_f16);
   a.M = M; a.N = N; a.K = K; a.G = K / kGroup;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (use_stream(M)) {
+    StreamArgs st{};
+    st.codes = a.codes; st.scalesT = a.scalesT; st.act = qa; st.sa = sa; st.y = a.y;
+    st.M = M; st.N = N; st.K = K; st.G = a.G;
+    launch_stream<true>(st, s);
+    return launch_status();
+  }
   const SmallPlan plan = plan_small<true>(M, N, K);
   if (plan.use) {
     SmallArgs sa_{};
@@ -295,6 +352,13 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16, int M, int N, int K,
   a.y = static_cast<uint16_t*>(y_f16);
   a.M = M; a.N = N; a.K = K; a.G = K / kGroup;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (use_stream(M)) {
+    StreamArgs st{};
+    st.codes = a.codes; st.scalesT = a.scalesT; st.act = x_f16; st.y = a.y;
+    st.M = M; st.N = N; st.K = K; st.G = a.G;
+    launch_stream<false>(st, s);
+    return launch_status();
+  }
   const SmallPlan plan = plan_small<false>(M, N, K);
   if (plan.use) {
     SmallArgs sa_{};

@@ -42,7 +42,10 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const uint4* __restrict_
     }
   }
   if (live) {
-    qa_words[idx] = w;
+    // word position inside the group: k-word kw = 4i + kb is stored at 4kb + i, so
+    // that the 16 bytes a GEMM lane (k-block kb) needs are contiguous
+    const size_t kw = idx & 15;
+    qa_words[(idx & ~(size_t)15) + ((kw & 3) << 2) + (kw >> 2)] = w;
     if ((threadIdx.x & 15) == 0) sa[idx >> 4] = s;
   }
 }

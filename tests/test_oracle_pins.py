@@ -93,8 +93,7 @@ def test_canonical_pack_hand_examples():
         if kind == "canonical":
             assert int(orc.pack_nibbles(codes)[0, 0]) == want
         else:
-            got = lay.act_bytes(codes)[0]
-            assert int.from_bytes(bytes(got.tolist()), "little") == want
+            assert int(lay.pack_words(codes)[0, 0]) == want
 
 
 def test_canonical_pack_roundtrip_all_pairs():
@@ -147,12 +146,20 @@ def test_weight_blob_roundtrip_and_tile_locality():
             assert np.array_equal(np.sort(nibs), np.sort(want))
 
 
-def test_act_bytes_roundtrip():
+def test_act_bytes_roundtrip_and_word_order():
     rng = np.random.default_rng(2)
     codes = rng.integers(-8, 8, size=(5, 256), dtype=np.int8)
     b = lay.act_bytes(codes)
     assert b.shape == (5, 128) and b.dtype == np.uint8
     assert np.array_equal(lay.decode_act_bytes(b), codes)
+    # word of codes [32i + 8kb, +8) of group g sits at word position 16g + 4kb + i
+    words = lay.pack_words(codes)
+    stored = b.view("<u4")
+    for m in range(5):
+        for g in range(2):
+            for i in range(4):
+                for kb in range(4):
+                    assert stored[m, 16 * g + 4 * kb + i] == words[m, 16 * g + 4 * i + kb]
 
 
 # ================================================================ O2 quant_act
