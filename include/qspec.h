@@ -137,6 +137,15 @@ int qspec_gemm_w4a4_partials(const void* packed, const uint8_t* qa,
                              int M, int N, int K, int group,
                              int n0, int n_count, int32_t* partials, void* stream);
 
+/*
+ * Debug entry: name of the device kernel the GEMM entry points select for an
+ * (M,N,K) problem, e.g. "gemm_stream_kernel<false, 2, 3>" (mode 0 = W4A16
+ * verify, 1 = W4A4 draft).  It matches the symbol a profiler reports, so that
+ * benchmark timings can be set beside profiler output.  Writes a NUL-terminated
+ * string of at most cap-1 characters to `out` (host memory); returns a status.
+ */
+int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* out, size_t cap);
+
 #ifdef __cplusplus
 }
 #endif

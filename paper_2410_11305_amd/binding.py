@@ -18,7 +18,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_WORKSPACE, ERR_HIP, ERR_UNSUPPORTED = ra
 EXPORTS = (
     "qspec_status_string", "qspec_version", "qspec_packed_weight_bytes", "qspec_workspace_bytes",
     "qspec_pack_weights", "qspec_unpack_weights", "qspec_quant_act", "qspec_gemm_w4a4",
-    "qspec_gemm_w4a16", "qspec_gemm_w4a4_partials",
+    "qspec_gemm_w4a16", "qspec_gemm_w4a4_partials", "qspec_describe_kernel",
 )
 
 
@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
     L.qspec_gemm_w4a16.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
     L.qspec_gemm_w4a4_partials.restype = ci
     L.qspec_gemm_w4a4_partials.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp]
+    L.qspec_describe_kernel.restype = ci
+    L.qspec_describe_kernel.argtypes = [ci, ci, ci, ci, ci, ctypes.c_char_p, sz]
     _lib = L
     return L
 
@@ -80,6 +82,12 @@ def packed_weight_bytes(N: int, K: int, group: int = GROUP) -> int:
 
 def workspace_bytes(M: int, N: int, K: int, group: int = GROUP) -> int:
     return lib().qspec_workspace_bytes(M, N, K, group)
+
+
+def describe_kernel(w4a4: bool, M: int, N: int, K: int, group: int = GROUP) -> str:
+    buf = ctypes.create_string_buffer(128)
+    _check(lib().qspec_describe_kernel(1 if w4a4 else 0, M, N, K, group, buf, 128), "qspec_describe_kernel")
+    return buf.value.decode()
 
 
 def _dev(t: torch.Tensor, dtype, name: str) -> int:

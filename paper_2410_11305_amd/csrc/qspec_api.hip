@@ -397,4 +397,19 @@ int qspec_gemm_w4a4_partials(const void* packed, const uint8_t* qa, int M, int N
   return launch_status();
 }
 
+int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* out, size_t cap) {
+  if (!out || cap == 0) return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, N, K, group)) return st;
+  const char* b = mode_w4a4 ? "true" : "false";
+  if (use_stream(M)) {
+    snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, M <= 16 ? 1 : 2, stream_nt(N));
+  } else {
+    const SmallPlan p = mode_w4a4 ? plan_small<true>(M, N, K) : plan_small<false>(M, N, K);
+    if (p.use) snprintf(out, cap, "gemm_small_kernel<%s, %d, %d, %d, 8>", b, p.TM, p.WN, p.WK);
+    else if (mode_w4a4) snprintf(out, cap, "gemm_w4a4_generic<%d, 4, false>", pick_tm(M));
+    else snprintf(out, cap, "gemm_w4a16_generic<%d, 4>", pick_tm(M));
+  }
+  return QSPEC_OK;
+}
+
 }  // extern "C"
