@@ -111,7 +111,7 @@ def main() -> int:
     yd = [torch.empty((Md, lin.N), dtype=torch.float16, device=dev) for lin in lins]
     yv = [torch.empty((Mv, lin.N), dtype=torch.float16, device=dev) for lin in lins]
     ws_bytes = max([B.workspace_bytes(Md, l.N, l.K) for l in lins] + [B.workspace_bytes(Mv, l.N, l.K) for l in lins] + [16])
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    ws = B.alloc_workspace(ws_bytes)
 
     # one plain device copy of known size (256 MiB read + 256 MiB written): the
     # reference point that scales the FETCH_SIZE / WRITE_SIZE counters in profiles

@@ -109,13 +109,20 @@ def _check(status: int, where: str) -> None:
         raise QSpecError(status, where)
 
 
+def alloc_workspace(nbytes: int) -> torch.Tensor:
+    """A workspace for the GEMM entry points.  Zero-filled: the head of a workspace
+    holds arrival counters that must be zero before its first use (every call
+    leaves them zero again, so one workspace serves any number of calls in turn)."""
+    return torch.zeros(max(int(nbytes), 16), dtype=torch.uint8, device="cuda")
+
+
 def _workspace(M, N, K, group, workspace):
     need = workspace_bytes(M, N, K, group)
     if workspace is None:
         if need == 0:
             return None, 0
-        # convenience for tests: hot loops pass a preallocated workspace instead
-        workspace = torch.empty(need, dtype=torch.uint8, device="cuda")
+        # convenience for tests: hot loops pass a workspace from alloc_workspace instead
+        workspace = alloc_workspace(need)
     return _dev(workspace, torch.uint8, "workspace"), workspace.numel()
 
 

@@ -10,8 +10,9 @@
 
 #include "common.hpp"
 #include "gemm_generic.hpp"
-#include "gemm_small.hpp"
 #include "gemm_stream.hpp"
+#include "gemm_tile.hpp"
+#include "gemm_tile16.hpp"
 #include "pack.hpp"
 #include "quant_act.hpp"
 
@@ -69,104 +70,11 @@ void launch_w4a16(const GemmArgs& a, hipStream_t s) {
 }
 
 
-// ---------------------------------------------------------------- small-M plans
-// A plan fixes the workgroup shape (WN x WK wavefronts), the number of
-// K-chunks S and the LDS footprint.  It is a pure function of (mode, M, N, K),
-// so qspec_workspace_bytes and the GEMM entry points always agree.
-struct SmallPlan {
-  bool use;        // false: fall back to the generic kernel
-  int TM, WN, WK, S, gc_max;
-  size_t lds_bytes;
-};
-
-constexpr int kLdsCap = 64 * 1024;
-constexpr int kSmallMaxM = 32;
-
-// QSPEC_PLAN_W4A4 / QSPEC_PLAN_W4A16 = "WN,WK,S" override the heuristic
-// (benchmark A/B only; a plan that does not fit is ignored).
-bool plan_override(bool w4a4, int* wn, int* wk, int* s) {
-  const char* e = getenv(w4a4 ? "QSPEC_PLAN_W4A4" : "QSPEC_PLAN_W4A16");
-  if (!e) return false;
-  return sscanf(e, "%d,%d,%d", wn, wk, s) == 3;
+// QSPEC_KERNEL=generic routes M > 32 to the untiled reference kernels (benchmark A/B only)
+bool use_generic() {
+  const char* e = getenv("QSPEC_KERNEL");
+  return e && strcmp(e, "generic") == 0;
 }
-
-// One staging pass must cover a chunk: kStageU 16-byte pieces per thread and
-// row, one 8-byte scale piece per thread, two activation scales per thread.
-template <bool W4A4>
-bool small_stage_fits(int TM, int WN, int gc_max) {
-  const int tpr = 512 / (TM * 16);
-  if (gc_max * (W4A4 ? 4 : 16) > tpr * kStageU) return false;
-  if (gc_max * WN * 4 > 512) return false;
-  if (W4A4 && gc_max * TM * 16 > 1024) return false;
-  return true;
-}
-
-template <bool W4A4>
-size_t small_lds_bytes(int TM, int WN, int WK, int gc_max) {
-  if (!small_stage_fits<W4A4>(TM, WN, gc_max)) return (size_t)1 << 30;
-  size_t total = TM == 1 ? (size_t)SmallLds<W4A4, 1>(gc_max, WN).total : (size_t)SmallLds<W4A4, 2>(gc_max, WN).total;
-  const size_t red = WK > 1 ? (size_t)WK * WN * TM * 4 * 64 * 4 : 0;
-  return total > red ? total : red;
-}
-
-template <bool W4A4>
-SmallPlan plan_small(int M, int N, int K) {
-  SmallPlan p{};
-  const int G = K / kGroup;
-  if (M > kSmallMaxM) return p;
-  p.TM = M <= 16 ? 1 : 2;
-  int wn = W4A4 ? 1 : 8, wk = W4A4 ? 8 : 1, s = 0;
-  const bool forced = plan_override(W4A4, &wn, &wk, &s);
-  const bool shape_ok = (wn == 1 || wn == 2 || wn == 4 || wn == 8) && wn * wk == 8;
-  if (!shape_ok) { wn = W4A4 ? 1 : 8; wk = 8 / wn; s = 0; }
-  p.WN = wn; p.WK = wk;
-  const int NB = (N / 16 + wn - 1) / wn;
-  // smallest S whose chunk fits the LDS cap
-  int s_min = 1;
-  while (s_min < G && small_lds_bytes<W4A4>(p.TM, wn, wk, (G + s_min - 1) / s_min) > (size_t)kLdsCap) ++s_min;
-  if (small_lds_bytes<W4A4>(p.TM, wn, wk, (G + s_min - 1) / s_min) > (size_t)kLdsCap) return p;
-  if (!(forced && s >= s_min && s <= G)) {
-    const int target = 512;                 // about two workgroups per CU
-    s = (target + NB / 2) / NB;
-    if (s < s_min) s = s_min;
-    if (s > G) s = G;
-    if (W4A4 && s_min == 1 && NB >= 256) s = 1;
-  }
-  p.S = s;
-  p.gc_max = (G + s - 1) / s;
-  p.lds_bytes = small_lds_bytes<W4A4>(p.TM, wn, wk, p.gc_max);
-  p.use = true;
-  return p;
-}
-
-template <bool W4A4, int TM, int WN, int WK>
-void launch_small_inst(const SmallArgs& a, size_t lds, hipStream_t s) {
-  dim3 grid((a.N / 16 + WN - 1) / WN, a.S);
-  hipLaunchKernelGGL((gemm_small_kernel<W4A4, TM, WN, WK, 8>), grid, dim3(WN * WK * 64), lds, s, a);
-}
-
-template <bool W4A4, int TM>
-void launch_small_tm(const SmallPlan& p, const SmallArgs& a, hipStream_t s) {
-  switch (p.WN) {
-    case 1: launch_small_inst<W4A4, TM, 1, 8>(a, p.lds_bytes, s); break;
-    case 2: launch_small_inst<W4A4, TM, 2, 4>(a, p.lds_bytes, s); break;
-    case 4: launch_small_inst<W4A4, TM, 4, 2>(a, p.lds_bytes, s); break;
-    default: launch_small_inst<W4A4, TM, 8, 1>(a, p.lds_bytes, s); break;
-  }
-}
-
-template <bool W4A4>
-void launch_small(const SmallPlan& p, SmallArgs a, hipStream_t s) {
-  a.S = p.S;
-  a.gc_max = p.gc_max;
-  if (p.TM == 1) launch_small_tm<W4A4, 1>(p, a, s); else launch_small_tm<W4A4, 2>(p, a, s);
-  if (p.S > 1) {
-    const size_t n_quads = (size_t)a.M * a.N / 4;
-    hipLaunchKernelGGL(splitk_finish_kernel, dim3(blocks_for(n_quads, 256)), dim3(256), 0, s,
-                       reinterpret_cast<const float4*>(a.ws), reinterpret_cast<uint2*>(a.y), n_quads, p.S);
-  }
-}
-
 
 // ---------------------------------------------------------------- streaming (small-M) kernel
 constexpr int kStreamMaxM = 32;
@@ -190,11 +98,7 @@ int stream_nt(int N) {
   return best;
 }
 
-bool use_stream(int M) {
-  if (M > kStreamMaxM) return false;
-  const char* e = getenv("QSPEC_KERNEL");
-  return !(e && strcmp(e, "small") == 0);
-}
+bool use_stream(int M) { return M <= kStreamMaxM; }
 
 template <bool W4A4, int TM>
 void launch_stream_tm(const StreamArgs& a, int nt, hipStream_t s) {
@@ -214,8 +118,122 @@ void launch_stream(const StreamArgs& a, hipStream_t s) {
   if (a.M <= 16) launch_stream_tm<W4A4, 1>(a, nt, s); else launch_stream_tm<W4A4, 2>(a, nt, s);
 }
 
-inline size_t plan_ws_bytes(const SmallPlan& p, int M, int N) {
-  return p.use && p.S > 1 ? (size_t)p.S * M * N * 4 : 0;
+// ---------------------------------------------------------------- tiled (M > 32) kernels
+// Workgroup shapes the tiled kernels are instantiated for: TN x TMW MFMA tiles per
+// wavefront, WGN x WGM wavefronts per workgroup, weight ring of NW groups (verify
+// mode), OCC workgroups per compute unit (the register budget the compiler is held to).
+struct TileShape { int TN, TMW, WGN, WGM, NW, OCC; };
+constexpr TileShape kShapes16[] = {     // verify mode (gemm_tile16_kernel)
+    {4, 8, 4, 1, 2, 2},   // 0: 256 outputs x 128 tokens
+    {2, 8, 4, 1, 4, 2},   // 1: 128 x 128, tall wave tiles
+    {4, 4, 2, 2, 2, 2},   // 2: 128 x 128, square wave tiles
+    {2, 4, 4, 1, 4, 3},   // 3: 128 x 64
+    {4, 4, 4, 1, 2, 2},   // 4: 256 x 64
+    {3, 2, 1, 4, 4, 2},   // 5: 48 x 128
+    {4, 8, 4, 1, 4, 2},   // 6: as 0 with a deeper ring
+};
+constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile_kernel)
+    {4, 8, 4, 1, 3, 2},   // 0: 256 outputs x 128 tokens
+    {4, 4, 2, 2, 3, 2},   // 1: 128 x 128
+    {4, 8, 2, 2, 3, 1},   // 2: 128 x 256
+    {2, 4, 4, 1, 3, 2},   // 3: 128 x 64
+    {4, 4, 4, 1, 3, 2},   // 4: 256 x 64
+    {2, 8, 4, 1, 3, 2},   // 5: 128 x 128, tall wave tiles
+    {3, 2, 1, 4, 3, 2},   // 6: 48 x 128
+};
+constexpr int kNumTileShapes = 7;
+constexpr size_t kTicketBytes = 16384;                 // head of the workspace: arrival counters
+constexpr int kMaxTickets = (int)(kTicketBytes / 4);
+
+struct TilePlan {
+  int shape;      // index into the mode's shape table
+  int S;          // K-slices
+  int nb, mb;     // output blocks
+};
+
+inline const TileShape& shape_of(bool w4a4, int i) { return w4a4 ? kShapes4[i] : kShapes16[i]; }
+
+// QSPEC_TILE_W4A4 / QSPEC_TILE_W4A16 = "shape,S" override the heuristic (benchmark A/B only).
+bool tile_override(bool w4a4, int* shape, int* S) {
+  const char* e = getenv(w4a4 ? "QSPEC_TILE_W4A4" : "QSPEC_TILE_W4A16");
+  if (!e) return false;
+  if (sscanf(e, "%d,%d", shape, S) != 2) return false;
+  return *shape >= 0 && *shape < kNumTileShapes && *S >= 1;
+}
+
+// Pure function of (mode, M, N, K): qspec_workspace_bytes and the GEMM entry points agree.
+TilePlan plan_tile(bool w4a4, int M, int N, int K) {
+  const int G = K / kGroup;
+  TilePlan p{};
+  int shape = 0, S = 1;
+  if (!tile_override(w4a4, &shape, &S)) {
+    shape = M <= 64 ? 3 : 1;
+    S = 1;
+  }
+  const TileShape& t = shape_of(w4a4, shape);
+  const int bn = 16 * t.TN * t.WGN, bm = 16 * t.TMW * t.WGM;
+  p.shape = shape;
+  p.nb = (N + bn - 1) / bn;
+  p.mb = (M + bm - 1) / bm;
+  if (S > G) S = G;
+  if (p.nb * p.mb > kMaxTickets) S = 1;
+  p.S = S;
+  return p;
+}
+
+inline size_t plan_ws_bytes(const TilePlan& p, int M, int N) {
+  return p.S > 1 ? kTicketBytes + (size_t)p.S * M * N * 4 : 0;
+}
+
+template <int TN, int TMW, int WGN, int WGM, int NW, int OCC>
+int launch_tile4_inst(const TileArgs& a, hipStream_t s) {
+  using C = TileCfg<true, TN, TMW, WGN, WGM>;
+  auto kern = gemm_tile_kernel<true, TN, TMW, WGN, WGM, OCC>;
+  if (C::kLdsBytes > 64 * 1024) {
+    static bool raised = false;       // the default cap on dynamic LDS is 64 KiB
+    if (!raised) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              C::kLdsBytes) != hipSuccess)
+        return QSPEC_ERR_HIP;
+      raised = true;
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3(a.nb * a.mb * a.S), dim3(C::kThreads), C::kLdsBytes, s, a);
+  return QSPEC_OK;
+}
+
+template <int TN, int TMW, int WGN, int WGM, int NW, int OCC>
+int launch_tile16_inst(const TileArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL((gemm_tile16_kernel<TN, TMW, WGN, WGM, NW, OCC>), dim3(a.nb * a.mb * a.S),
+                     dim3(64 * WGN * WGM), 0, s, a);
+  return QSPEC_OK;
+}
+
+template <bool W4A4>
+int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s) {
+  a.S = plan.S; a.nb = plan.nb; a.mb = plan.mb;
+  a.tickets = static_cast<unsigned*>(workspace);
+  a.ws = plan.S > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kTicketBytes) : nullptr;
+  if (W4A4) {
+    switch (plan.shape) {
+      case 0: return launch_tile4_inst<4, 8, 4, 1, 3, 2>(a, s);
+      case 1: return launch_tile4_inst<4, 4, 2, 2, 3, 2>(a, s);
+      case 2: return launch_tile4_inst<4, 8, 2, 2, 3, 1>(a, s);
+      case 3: return launch_tile4_inst<2, 4, 4, 1, 3, 2>(a, s);
+      case 4: return launch_tile4_inst<4, 4, 4, 1, 3, 2>(a, s);
+      case 5: return launch_tile4_inst<2, 8, 4, 1, 3, 2>(a, s);
+      default: return launch_tile4_inst<3, 2, 1, 4, 3, 2>(a, s);
+    }
+  }
+  switch (plan.shape) {
+    case 0: return launch_tile16_inst<4, 8, 4, 1, 2, 2>(a, s);
+    case 1: return launch_tile16_inst<2, 8, 4, 1, 4, 2>(a, s);
+    case 2: return launch_tile16_inst<4, 4, 2, 2, 2, 2>(a, s);
+    case 3: return launch_tile16_inst<2, 4, 4, 1, 4, 3>(a, s);
+    case 4: return launch_tile16_inst<4, 4, 4, 1, 2, 2>(a, s);
+    case 5: return launch_tile16_inst<3, 2, 1, 4, 4, 2>(a, s);
+    default: return launch_tile16_inst<4, 8, 4, 1, 4, 2>(a, s);
+  }
 }
 
 }  // namespace
@@ -244,9 +262,9 @@ size_t qspec_packed_weight_bytes(int N, int K, int group) {
 
 size_t qspec_workspace_bytes(int M, int N, int K, int group) {
   if (check_shape(M, N, K, group) != QSPEC_OK) return 0;
-  if (use_stream(M)) return 0;
-  const size_t a = plan_ws_bytes(plan_small<true>(M, N, K), M, N);
-  const size_t b = plan_ws_bytes(plan_small<false>(M, N, K), M, N);
+  if (use_stream(M) || use_generic()) return 0;
+  const size_t a = plan_ws_bytes(plan_tile(true, M, N, K), M, N);
+  const size_t b = plan_ws_bytes(plan_tile(false, M, N, K), M, N);
   return a > b ? a : b;
 }
 
@@ -319,13 +337,11 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int 
     launch_stream<true>(st, s);
     return launch_status();
   }
-  const SmallPlan plan = plan_small<true>(M, N, K);
-  if (plan.use) {
-    SmallArgs sa_{};
-    sa_.codes = a.codes; sa_.scalesT = a.scalesT; sa_.act = qa; sa_.sa = sa; sa_.y = a.y;
-    sa_.ws = static_cast<float*>(workspace);
-    sa_.M = M; sa_.N = N; sa_.K = K; sa_.G = a.G;
-    launch_small<true>(plan, sa_, s);
+  if (!use_generic()) {
+    TileArgs t{};
+    t.codes = a.codes; t.scalesT = a.scalesT; t.act = qa; t.sa = sa; t.y = a.y;
+    t.M = M; t.N = N; t.K = K; t.G = a.G;
+    if (int st = launch_tile<true>(plan_tile(true, M, N, K), t, workspace, s)) return st;
     return launch_status();
   }
   switch (pick_tm(M)) {
@@ -359,13 +375,11 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16, int M, int N, int K,
     launch_stream<false>(st, s);
     return launch_status();
   }
-  const SmallPlan plan = plan_small<false>(M, N, K);
-  if (plan.use) {
-    SmallArgs sa_{};
-    sa_.codes = a.codes; sa_.scalesT = a.scalesT; sa_.act = x_f16; sa_.y = a.y;
-    sa_.ws = static_cast<float*>(workspace);
-    sa_.M = M; sa_.N = N; sa_.K = K; sa_.G = a.G;
-    launch_small<false>(plan, sa_, s);
+  if (!use_generic()) {
+    TileArgs t{};
+    t.codes = a.codes; t.scalesT = a.scalesT; t.act = x_f16; t.y = a.y;
+    t.M = M; t.N = N; t.K = K; t.G = a.G;
+    if (int st = launch_tile<false>(plan_tile(false, M, N, K), t, workspace, s)) return st;
     return launch_status();
   }
   switch (pick_tm(M)) {
@@ -404,9 +418,11 @@ int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* o
   if (use_stream(M)) {
     snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, M <= 16 ? 1 : 2, stream_nt(N));
   } else {
-    const SmallPlan p = mode_w4a4 ? plan_small<true>(M, N, K) : plan_small<false>(M, N, K);
-    if (p.use) snprintf(out, cap, "gemm_small_kernel<%s, %d, %d, %d, 8>", b, p.TM, p.WN, p.WK);
-    else if (mode_w4a4) snprintf(out, cap, "gemm_w4a4_generic<%d, 4, false>", pick_tm(M));
+    if (!use_generic()) {
+      const TileShape& t = shape_of(mode_w4a4 != 0, plan_tile(mode_w4a4 != 0, M, N, K).shape);
+      if (mode_w4a4) snprintf(out, cap, "gemm_tile_kernel<true, %d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.OCC);
+      else snprintf(out, cap, "gemm_tile16_kernel<%d, %d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.NW, t.OCC);
+    } else if (mode_w4a4) snprintf(out, cap, "gemm_w4a4_generic<%d, 4, false>", pick_tm(M));
     else snprintf(out, cap, "gemm_w4a16_generic<%d, 4>", pick_tm(M));
   }
   return QSPEC_OK;

@@ -192,6 +192,62 @@ def test_all_sixteen_codes_dequantise_exactly(env):
     assert np.array_equal(y, (qw.T.astype(np.float32) * 0.5).astype(np.float16))
 
 
+# ------------------------------------------------------------------ tiled kernels (M > 32)
+@pytest.mark.parametrize("S", [1, 3])
+@pytest.mark.parametrize("shape", range(7))
+def test_tile_kernels_every_workgroup_shape(env, monkeypatch, shape, S):
+    """Every instantiated workgroup shape, alone and with 3 K-slices that meet in
+    the workspace, on a problem with ragged M, a ragged last n-block and a group
+    count (7) that does not divide by the slice count."""
+    torch, B = env
+    M, N, K = 150, 304, 896
+    monkeypatch.setenv("QSPEC_TILE_W4A4", f"{shape},{S}")
+    monkeypatch.setenv("QSPEC_TILE_W4A16", f"{shape},{S}")
+    codes, scales, x = synth.generic_case(600 + shape, M, N, K)
+    blob = B.pack_weights(dev(torch, codes), dev(torch, scales))
+    qa, sa, q_ref, s_ref = _check_quant(torch, B, x)
+    need = B.workspace_bytes(M, N, K)
+    assert (need > 0) == (S > 1)
+    ws = B.alloc_workspace(need)
+    ref4 = orc.gemm_w4a4(q_ref, s_ref, codes, scales)
+    ref16 = orc.gemm_w4a16(x, codes, scales)
+    xd = dev(torch, x)
+    outs = []
+    for _ in range(2):                      # the second call finds the counters as the first left them
+        y4 = B.gemm_w4a4(blob, qa, sa, N, workspace=ws)
+        y16 = B.gemm_w4a16(blob, xd, N, workspace=ws)
+        torch.cuda.synchronize()
+        assert rel_err(y4.cpu().numpy(), ref4) <= TOL
+        assert rel_err(y16.cpu().numpy(), ref16) <= TOL
+        outs.append((y4, y16))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    if S > 1:
+        assert int(ws[:16384].count_nonzero()) == 0
+
+
+def test_tile_kernel_exact_cases(env, monkeypatch):
+    """Exactly representable products through the tiled kernels with K-slices:
+    any summation order must give the oracle's bits."""
+    torch, B = env
+    M, N, K = 100, 96, 512
+    monkeypatch.setenv("QSPEC_TILE_W4A4", "1,2")
+    monkeypatch.setenv("QSPEC_TILE_W4A16", "1,2")
+    rng = np.random.default_rng(8)
+    x = rng.integers(-2, 3, size=(M, K)).astype(np.float16)
+    qw = rng.integers(-8, 8, size=(N, K), dtype=np.int8)
+    sw = np.tile(np.array([[2.0 ** -6, 2.0 ** -5, 2.0 ** -7, 2.0 ** -6]], np.float16), (N, 1))
+    blob = B.pack_weights(dev(torch, qw), dev(torch, sw))
+    y = B.gemm_w4a16(blob, dev(torch, x), N).cpu().numpy()
+    assert np.array_equal(y, orc.gemm_w4a16(x, qw, sw))
+    q = rng.integers(-2, 3, size=(M, K), dtype=np.int8)
+    qs = rng.integers(-2, 3, size=(N, K), dtype=np.int8)
+    ones_w = np.ones((N, K // 128), np.float16)
+    ones_a = np.ones((M, K // 128), np.float32)
+    blob = B.pack_weights(dev(torch, qs), dev(torch, ones_w))
+    y = B.gemm_w4a4(blob, dev(torch, lay.act_bytes(q)), dev(torch, ones_a), N).cpu().numpy()
+    assert np.array_equal(y.astype(np.int64), q.astype(np.int64) @ qs.astype(np.int64).T)
+
+
 # ------------------------------------------------------------------ the five configurations
 def _sample_cols(N, count, seed):
     if N <= count:
