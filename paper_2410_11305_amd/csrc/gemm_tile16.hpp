@@ -243,4 +243,287 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile16_kernel(TileAr
   tile_store<TN, TMW>(p, tc, acc, T0, m0 + mw0);
 }
 
+// ---------------------------------------------------------------------------
+// The same kernel on v_mfma_f32_32x32x16_f16: half as many matrix instructions
+// for the same arithmetic (a wavefront issues them at a better rate) and half
+// the dequantised-operand registers.  A wavefront owns PN x PM tiles of 32 x 32.
+//
+// A operand (32 rows x 16 k): lane l supplies 8 consecutive k of row l % 32,
+// lanes 0..31 the first 8 k of the step, lanes 32..63 the second 8.  In the blob
+// the 16 bytes of tile lane (r, kb) are words i = 0..3 holding k-chunks (8 k each)
+// 4i + kb.  So lane l = (h = l / 32, row = l % 32) fetches, from the 16-row tile
+// that holds its row, the 16 bytes of tile lane (row % 16, h) ["lo"] and of tile
+// lane (row % 16, h + 2) ["hi"]: word i of lo is chunk 4i + h, word i of hi is
+// chunk 4i + 2 + h, and step s = 2i + e (e = 0: lo, 1: hi) covers the 16
+// consecutive k = 32i + 16e .. +15.  The B operand of that step is, for lane
+// (h, m = l % 32), chunk 4i + 2e + h of token row m.
+// D: lane holds column m = l % 32 and rows 8a + 4h + r (a, r = 0..3) in
+// register 4a + r: four runs of four consecutive output features.
+template <int PN, int PM>
+__device__ __forceinline__ void tile_store32(const TileArgs& p, const TileCoord& tc, float (&acc)[PN][PM][16],
+                                             int n0, int mrow0) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int m32 = lane & 31, h = lane >> 5;
+  if (p.S == 1) {
+#pragma unroll
+    for (int j = 0; j < PN; ++j)
+#pragma unroll
+      for (int t = 0; t < PM; ++t) {
+        const int m = mrow0 + 32 * t + m32;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          const int n = n0 + 32 * j + 8 * a + 4 * h;
+          if (m < p.M && n < p.N) {
+            uint2 out;
+            out.x = (uint32_t)float_to_half_bits(acc[j][t][4 * a + 0]) | ((uint32_t)float_to_half_bits(acc[j][t][4 * a + 1]) << 16);
+            out.y = (uint32_t)float_to_half_bits(acc[j][t][4 * a + 2]) | ((uint32_t)float_to_half_bits(acc[j][t][4 * a + 3]) << 16);
+            *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + n) = out;
+          }
+        }
+      }
+    return;
+  }
+  const size_t slice_elems = (size_t)p.M * p.N;
+#pragma unroll
+  for (int j = 0; j < PN; ++j)
+#pragma unroll
+    for (int t = 0; t < PM; ++t) {
+      const int m = mrow0 + 32 * t + m32;
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int n = n0 + 32 * j + 8 * a + 4 * h;
+        if (m < p.M && n < p.N)
+          *reinterpret_cast<float4*>(p.ws + tc.slice * slice_elems + (size_t)m * p.N + n) =
+              float4{acc[j][t][4 * a + 0], acc[j][t][4 * a + 1], acc[j][t][4 * a + 2], acc[j][t][4 * a + 3]};
+      }
+    }
+  __threadfence();                      // this thread's partial sums are visible device-wide ...
+  __syncthreads();                      // ... for every thread of the workgroup, before the ticket is taken
+  __shared__ unsigned ticket32;
+  if (tid == 0) {
+    const unsigned blk = (unsigned)(tc.nblk * p.mb + tc.mblk);
+    const unsigned old = atomicAdd(&p.tickets[blk], 1u);
+    if (old == (unsigned)p.S - 1) atomicExch(&p.tickets[blk], 0u);   // nobody else touches it any more in this launch
+    ticket32 = old;
+  }
+  __syncthreads();
+  if (ticket32 != (unsigned)p.S - 1) return;
+  __threadfence();                      // the other slices' stores are visible to the loads below
+#pragma unroll
+  for (int j = 0; j < PN; ++j)
+#pragma unroll
+    for (int t = 0; t < PM; ++t) {
+      const int m = mrow0 + 32 * t + m32;
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int n = n0 + 32 * j + 8 * a + 4 * h;
+        if (m < p.M && n < p.N) {
+          const size_t o = (size_t)m * p.N + n;
+          float4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+          for (int c = 0; c < p.S; ++c) {       // fixed order: the result does not depend on who came last
+            const float4 v = *reinterpret_cast<const float4*>(p.ws + c * slice_elems + o);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+          }
+          uint2 out;
+          out.x = (uint32_t)float_to_half_bits(s.x) | ((uint32_t)float_to_half_bits(s.y) << 16);
+          out.y = (uint32_t)float_to_half_bits(s.z) | ((uint32_t)float_to_half_bits(s.w) << 16);
+          *reinterpret_cast<uint2*>(p.y + o) = out;
+        }
+      }
+    }
+}
+
+template <int PN, int PM, int WGN, int WGM, int NW, int OCC>
+__global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile16w_kernel(TileArgs p) {
+  constexpr int kWaves = WGN * WGM;
+  constexpr int BM = 32 * PM * WGM;
+  constexpr int kStageBytes = BM * 256;
+  constexpr int U = kStageBytes / 1024 / kWaves;       // wave-wide transfers per wave and group
+  static_assert(kStageBytes % (1024 * kWaves) == 0, "the stage divides evenly among the waves");
+  static_assert(NW == 2 || NW == 4, "the stage of a group must follow from its ring slot");
+  static_assert(kWaves == 4 || kWaves == 8, "row % 16 of a transfer must not depend on u");
+  __shared__ __attribute__((aligned(1024))) uint8_t xs0[kStageBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t xs1[kStageBytes];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wn = wave % WGN, wm = wave / WGN;
+  const int m32 = lane & 31, h = lane >> 5;
+  const int G = p.G;
+  const TileCoord tc = tile_coord(p);
+  const int g0 = tc.g0, g1 = tc.g1;
+  const int tilesN = p.N >> 4;
+  const int n0 = (tc.nblk * (PN * WGN) + wn * PN) * 32;      // first output feature of this wave
+  const int m0 = tc.mblk * BM;
+  const int mw0 = wm * (PM * 32);
+
+  const rsrc_t r_codes = make_rsrc(p.codes, (uint32_t)((size_t)p.N * p.K / 2));
+  const rsrc_t r_scales = make_rsrc(p.scalesT, (uint32_t)((size_t)p.N * G * 2));
+  const rsrc_t r_act = make_rsrc(p.act, (uint32_t)((size_t)p.M * p.K * 2));
+  auto past_end = [&](int g) -> uint32_t { return (uint32_t)((g1 - 1 - g) >> 31) << 31; };
+
+  // ---- activations: global -> LDS, as in gemm_tile16_kernel
+  const int row_in_blk = 4 * wave + (lane >> 4);
+  const uint32_t x_voff = (uint32_t)(m0 + row_in_blk) * (uint32_t)p.K * 2u +
+                          (uint32_t)(((lane & 15) ^ (row_in_blk & 15)) << 4);
+  const uint32_t x_ustep = (uint32_t)(4 * kWaves) * (uint32_t)p.K * 2u;
+  auto dma_x = [&](int g, uint8_t* stage) {
+    const uint32_t gbase = (uint32_t)g * 256u + past_end(g);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t off = x_voff + (gbase + (uint32_t)u * x_ustep);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_act, (lds_ptr_t)(stage + (wave + u * kWaves) * 1024), 16, off, 0, 0, 0);
+    }
+  };
+
+  // ---- weights: per 32-row pair two 16-byte pieces (lo, hi) and the row's scale
+  uint4 wlo[NW][PN], whi[NW][PN];
+  uint32_t sq[NW][PN];
+  // per-lane offsets of pair 0 inside a group (bit 31: the lane's tile lies past N;
+  // then so do the tiles of the pairs after it, and pair j adds a wave-uniform step)
+  const int n_lane = n0 + m32;          // this lane's weight row in pair 0
+  const uint32_t w_voff = (uint32_t)(n_lane >> 4) * G * 1024u + (uint32_t)((n_lane & 15) + 16 * h) * 16u;
+  auto load_w = [&](int d, int g) {
+    const uint32_t gone = past_end(g);
+#pragma unroll
+    for (int j = 0; j < PN; ++j) {
+      const uint32_t none = (uint32_t)((p.N - 1 - (n_lane + 32 * j)) >> 31) << 31;
+      const uint32_t skip = gone | none;
+      const uint32_t wo = w_voff + (uint32_t)(2 * j) * G * 1024u + (uint32_t)g * 1024u;
+      wlo[d][j] = buf_load16(r_codes, wo | skip);
+      whi[d][j] = buf_load16(r_codes, (wo + 512u) | skip);
+      sq[d][j] = buf_load_u16(r_scales, (((uint32_t)g * (uint32_t)p.N + (uint32_t)(n_lane + 32 * j)) * 2u) | skip);
+    }
+  };
+
+  float acc[PN][PM][16];
+#pragma unroll
+  for (int j = 0; j < PN; ++j)
+#pragma unroll
+    for (int t = 0; t < PM; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][t][r] = 0.0f;
+
+  // both stages start as zeros (see gemm_tile16_kernel)
+#pragma unroll
+  for (int o = tid * 16; o < kStageBytes; o += 64 * kWaves * 16) {
+    *reinterpret_cast<uint4*>(xs0 + o) = uint4{0u, 0u, 0u, 0u};
+    *reinterpret_cast<uint4*>(xs1 + o) = uint4{0u, 0u, 0u, 0u};
+  }
+  __syncthreads();
+  dma_x(g0, xs0);
+#pragma unroll
+  for (int d = 0; d < NW; ++d) load_w(d, g0 + d);
+
+  v2h s2[PN], s2n[PN], wa0[PN][4];
+#pragma unroll
+  for (int j = 0; j < PN; ++j) {
+    const _Float16 sc = __builtin_bit_cast(_Float16, (uint16_t)sq[0][j]);
+    s2[j] = v2h{sc, sc};
+    s2n[j] = s2[j];
+#pragma unroll
+    for (int hh = 0; hh < 4; ++hh) wa0[j][hh] = dequant_pair_scaled(wlo[0][j].x, hh, s2[j]);
+  }
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+  __builtin_amdgcn_s_barrier();
+
+  constexpr int Q = PN * PM;                   // MFMAs per k-step (16 k), one LDS read feeds PN of them
+  constexpr int P = 4 * PN;                    // dequantisation pieces per k-step
+  static_assert(Q >= P / 2, "at most two pieces between MFMAs");
+  constexpr int PER = (P + Q - 1) / Q;         // pieces after each MFMA
+
+  auto group_body = [&](auto slot_c, int g) __attribute__((always_inline)) {
+    constexpr int SLOT = decltype(slot_c)::value;
+    constexpr int NEXT = (SLOT + 1) % NW;
+    const uint8_t* xl = (SLOT & 1) ? xs1 : xs0;
+    uint8_t* xnext = (SLOT & 1) ? xs0 : xs1;
+    uint4 xb[2][PM];
+    auto read_step = [&](int s, uint4 (&dst)[PM]) {
+      const int c = 4 * (s >> 1) + 2 * (s & 1) + h;      // this lane's k-chunk of step s
+#pragma unroll
+      for (int t = 0; t < PM; ++t) {
+        const int row = mw0 + 32 * t + m32;
+        dst[t] = *reinterpret_cast<const uint4*>(xl + row * 256 + ((c ^ (row & 15)) << 4));
+      }
+    };
+    auto word_of_step = [&](int d, int j, int s) -> uint32_t {
+      const uint4& q = (s & 1) ? whi[d][j] : wlo[d][j];
+      return word_of(q, s >> 1);
+    };
+    read_step(0, xb[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    v2h wa[2][PN][4];                            // k-step s lives in wa[s & 1]
+#pragma unroll
+    for (int j = 0; j < PN; ++j)
+#pragma unroll
+      for (int hh = 0; hh < 4; ++hh) wa[0][j][hh] = wa0[j][hh];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      if (s + 1 < 8) read_step(s + 1, xb[(s + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s == 1) {
+        // the other stage was last read in the group before this one and every wave has
+        // passed the barrier that ended it; issued here rather than at the top so that
+        // the first MFMAs of the group do not queue behind eight address computations
+        dma_x(g + 1, xnext);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int q = 0; q < Q; ++q) {
+        const int t = q / PN, j = q % PN;
+        {
+          const v8h av = v8h{wa[s & 1][j][0].x, wa[s & 1][j][0].y, wa[s & 1][j][1].x, wa[s & 1][j][1].y,
+                             wa[s & 1][j][2].x, wa[s & 1][j][2].y, wa[s & 1][j][3].x, wa[s & 1][j][3].y};
+          const v8h xv = __builtin_bit_cast(v8h, xb[s & 1][t]);
+          v16f d;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) d[r] = acc[j][t][r];
+          d = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, xv, d, 0, 0, 0);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[j][t][r] = d[r];
+        }
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+          const int pp = q * PER + e;            // piece of the next k-step
+          if (pp < P) {
+            const int jj = pp / 4, hh = pp % 4;
+            if (s < 7) wa[(s + 1) & 1][jj][hh] = dequant_pair_scaled(word_of_step(SLOT, jj, s + 1), hh, s2[jj]);
+            else wa0[jj][hh] = dequant_pair_scaled(wlo[NEXT][jj].x, hh, s2n[jj]);
+          }
+        }
+        if (s == 6 && q + 1 == Q) {
+          // every word of this slot is in registers as fp16 now: refill it, and turn the
+          // next slot's scales (fetched NW-1 groups ago) into fp16 pairs
+          load_w(SLOT, g + NW);
+#pragma unroll
+          for (int jn = 0; jn < PN; ++jn) {
+            const _Float16 sn = __builtin_bit_cast(_Float16, (uint16_t)sq[NEXT][jn]);
+            s2n[jn] = v2h{sn, sn};
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < PN; ++j) s2[j] = s2n[j];
+    // Activation transfers were issued before this group's 3*PN ring loads, and loads
+    // complete in order: at most 3*PN outstanding means they have landed.  (No store
+    // may sit between them: stores complete out of order with loads, so this kernel
+    // must compile without register spills.)
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(3 * PN));
+    __builtin_amdgcn_s_barrier();
+  };
+
+  for (int g = g0; g < g1; g += NW) {
+    group_body(std::integral_constant<int, 0>{}, g);
+    group_body(std::integral_constant<int, 1>{}, g + 1);
+    if constexpr (NW > 2) group_body(std::integral_constant<int, 2 % NW>{}, g + 2);
+    if constexpr (NW > 2) group_body(std::integral_constant<int, 3 % NW>{}, g + 3);
+  }
+
+  tile_store32<PN, PM>(p, tc, acc, n0, m0 + mw0);
+}
+
 }  // namespace qspec

@@ -131,7 +131,14 @@ constexpr TileShape kShapes16[] = {     // verify mode (gemm_tile16_kernel)
     {4, 4, 4, 1, 2, 2},   // 4: 256 x 64
     {3, 2, 1, 4, 4, 2},   // 5: 48 x 128
     {4, 8, 4, 1, 4, 2},   // 6: as 0 with a deeper ring
+    // from here on gemm_tile16w_kernel (32x32x16 MFMA): TN, TMW count 32 x 32 tiles
+    {2, 4, 4, 1, 2, 2},   // 7: 256 x 128
+    {2, 4, 4, 1, 4, 2},   // 8: 256 x 128, deeper ring
+    {1, 4, 4, 1, 4, 2},   // 9: 128 x 128
+    {2, 2, 4, 1, 4, 2},   // 10: 256 x 64
+    {1, 2, 4, 1, 4, 3},   // 11: 128 x 64
 };
+constexpr int kFirstWide = 7;
 constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile_kernel)
     {4, 8, 4, 1, 3, 2},   // 0: 256 outputs x 128 tokens
     {4, 4, 2, 2, 3, 2},   // 1: 128 x 128
@@ -142,6 +149,7 @@ constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile_kernel)
     {3, 2, 1, 4, 3, 2},   // 6: 48 x 128
 };
 constexpr int kNumTileShapes = 7;
+constexpr int kNumShapes16 = 12;
 constexpr size_t kTicketBytes = 16384;                 // head of the workspace: arrival counters
 constexpr int kMaxTickets = (int)(kTicketBytes / 4);
 
@@ -158,7 +166,7 @@ bool tile_override(bool w4a4, int* shape, int* S) {
   const char* e = getenv(w4a4 ? "QSPEC_TILE_W4A4" : "QSPEC_TILE_W4A16");
   if (!e) return false;
   if (sscanf(e, "%d,%d", shape, S) != 2) return false;
-  return *shape >= 0 && *shape < kNumTileShapes && *S >= 1;
+  return *shape >= 0 && *shape < (w4a4 ? kNumTileShapes : kNumShapes16) && *S >= 1;
 }
 
 // Pure function of (mode, M, N, K): qspec_workspace_bytes and the GEMM entry points agree.
@@ -171,7 +179,8 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
     S = 1;
   }
   const TileShape& t = shape_of(w4a4, shape);
-  const int bn = 16 * t.TN * t.WGN, bm = 16 * t.TMW * t.WGM;
+  const int edge = !w4a4 && shape >= kFirstWide ? 32 : 16;      // MFMA tile edge
+  const int bn = edge * t.TN * t.WGN, bm = edge * t.TMW * t.WGM;
   p.shape = shape;
   p.nb = (N + bn - 1) / bn;
   p.mb = (M + bm - 1) / bm;
@@ -209,6 +218,13 @@ int launch_tile16_inst(const TileArgs& a, hipStream_t s) {
   return QSPEC_OK;
 }
 
+template <int PN, int PM, int WGN, int WGM, int NW, int OCC>
+int launch_tile16w_inst(const TileArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL((gemm_tile16w_kernel<PN, PM, WGN, WGM, NW, OCC>), dim3(a.nb * a.mb * a.S),
+                     dim3(64 * WGN * WGM), 0, s, a);
+  return QSPEC_OK;
+}
+
 template <bool W4A4>
 int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s) {
   a.S = plan.S; a.nb = plan.nb; a.mb = plan.mb;
@@ -232,7 +248,12 @@ int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s
     case 3: return launch_tile16_inst<2, 4, 4, 1, 4, 3>(a, s);
     case 4: return launch_tile16_inst<4, 4, 4, 1, 2, 2>(a, s);
     case 5: return launch_tile16_inst<3, 2, 1, 4, 4, 2>(a, s);
-    default: return launch_tile16_inst<4, 8, 4, 1, 4, 2>(a, s);
+    case 6: return launch_tile16_inst<4, 8, 4, 1, 4, 2>(a, s);
+    case 7: return launch_tile16w_inst<2, 4, 4, 1, 2, 2>(a, s);
+    case 8: return launch_tile16w_inst<2, 4, 4, 1, 4, 2>(a, s);
+    case 9: return launch_tile16w_inst<1, 4, 4, 1, 4, 2>(a, s);
+    case 10: return launch_tile16w_inst<2, 2, 4, 1, 4, 2>(a, s);
+    default: return launch_tile16w_inst<1, 2, 4, 1, 4, 3>(a, s);
   }
 }
 
@@ -421,7 +442,8 @@ int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* o
     if (!use_generic()) {
       const TileShape& t = shape_of(mode_w4a4 != 0, plan_tile(mode_w4a4 != 0, M, N, K).shape);
       if (mode_w4a4) snprintf(out, cap, "gemm_tile_kernel<true, %d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.OCC);
-      else snprintf(out, cap, "gemm_tile16_kernel<%d, %d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.NW, t.OCC);
+      else snprintf(out, cap, "gemm_tile16%s_kernel<%d, %d, %d, %d, %d, %d>",
+                    plan_tile(false, M, N, K).shape >= kFirstWide ? "w" : "", t.TN, t.TMW, t.WGN, t.WGM, t.NW, t.OCC);
     } else if (mode_w4a4) snprintf(out, cap, "gemm_w4a4_generic<%d, 4, false>", pick_tm(M));
     else snprintf(out, cap, "gemm_w4a16_generic<%d, 4>", pick_tm(M));
   }
