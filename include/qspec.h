@@ -14,7 +14,8 @@
  *
  * Conventions shared by every entry point
  *   - Every pointer is a DEVICE pointer owned by the caller, 16-byte aligned.
- *     The library allocates nothing and keeps no state between calls.
+ *     The library allocates nothing and keeps no state between calls (but see
+ *     the workspace rule below).
  *   - `stream` is a hipStream_t (NULL = the default stream).  All work is
  *     enqueued on it; the call returns without synchronising.
  *   - The return value is a qspec_status.  Arguments are validated on the
@@ -73,8 +74,14 @@ int qspec_version(void);
 size_t qspec_packed_weight_bytes(int N, int K, int group);
 
 /* Scratch the GEMM entry points need for an (M,N,K) problem (partial sums of
- * K-splits that several workgroups produce); 0 when none is needed.  Returns 0
- * for unsupported shapes as well (the GEMM call reports those). */
+ * K-slices that several workgroups produce); 0 when none is needed.  Returns 0
+ * for unsupported shapes as well (the GEMM call reports those).
+ * Workspace rule: the first 16 KiB of a workspace hold arrival counters.  They
+ * must be ZERO when the first GEMM call that uses the workspace is enqueued;
+ * every GEMM call leaves them zero again, so one zero-filled allocation serves
+ * any number of calls in turn.  The rest is scratch with no meaning between
+ * calls.  Two GEMM calls that may run at the same time (different streams) need
+ * a workspace each. */
 size_t qspec_workspace_bytes(int M, int N, int K, int group);
 
 /*
@@ -112,7 +119,7 @@ int qspec_quant_act(const void* x_f16, int M, int K, int group,
  *   qa, sa  from qspec_quant_act for the same (M,K);
  *   y_f16   out, fp16 [M,N];
  *   workspace  at least qspec_workspace_bytes(M,N,K,group) bytes (may be NULL
- *              when that is 0); contents are scratch.
+ *              when that is 0); see the workspace rule at qspec_workspace_bytes.
  */
 int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa,
                     int M, int N, int K, int group,

@@ -11,8 +11,8 @@
 #include "common.hpp"
 #include "gemm_generic.hpp"
 #include "gemm_stream.hpp"
-#include "gemm_tile.hpp"
 #include "gemm_tile16.hpp"
+#include "gemm_tile4.hpp"
 #include "pack.hpp"
 #include "quant_act.hpp"
 
@@ -70,6 +70,8 @@ void launch_w4a16(const GemmArgs& a, hipStream_t s) {
 }
 
 
+constexpr int kNumCU = 256;
+
 // QSPEC_KERNEL=generic routes M > 32 to the untiled reference kernels (benchmark A/B only)
 bool use_generic() {
   const char* e = getenv("QSPEC_KERNEL");
@@ -78,7 +80,6 @@ bool use_generic() {
 
 // ---------------------------------------------------------------- streaming (small-M) kernel
 constexpr int kStreamMaxM = 32;
-constexpr int kNumCU = 256;
 
 // n-tiles per workgroup: minimise rounds x work per round over the 256 CUs, prefer
 // the larger NT on a tie (the activation operand is re-used NT times).
@@ -120,36 +121,24 @@ void launch_stream(const StreamArgs& a, hipStream_t s) {
 
 // ---------------------------------------------------------------- tiled (M > 32) kernels
 // Workgroup shapes the tiled kernels are instantiated for: TN x TMW MFMA tiles per
-// wavefront, WGN x WGM wavefronts per workgroup, weight ring of NW groups (verify
-// mode), OCC workgroups per compute unit (the register budget the compiler is held to).
-struct TileShape { int TN, TMW, WGN, WGM, NW, OCC; };
-constexpr TileShape kShapes16[] = {     // verify mode (gemm_tile16_kernel)
-    {4, 8, 4, 1, 2, 2},   // 0: 256 outputs x 128 tokens
-    {2, 8, 4, 1, 4, 2},   // 1: 128 x 128, tall wave tiles
-    {4, 4, 2, 2, 2, 2},   // 2: 128 x 128, square wave tiles
-    {2, 4, 4, 1, 4, 3},   // 3: 128 x 64
-    {4, 4, 4, 1, 2, 2},   // 4: 256 x 64
-    {3, 2, 1, 4, 4, 2},   // 5: 48 x 128
-    {4, 8, 4, 1, 4, 2},   // 6: as 0 with a deeper ring
-    // from here on gemm_tile16w_kernel (32x32x16 MFMA): TN, TMW count 32 x 32 tiles
-    {2, 4, 4, 1, 2, 2},   // 7: 256 x 128
-    {2, 4, 4, 1, 4, 2},   // 8: 256 x 128, deeper ring
-    {1, 4, 4, 1, 4, 2},   // 9: 128 x 128
-    {2, 2, 4, 1, 4, 2},   // 10: 256 x 64
-    {1, 2, 4, 1, 4, 3},   // 11: 128 x 64
+// wavefront, WGN x WGM wavefronts per workgroup, weight ring of NW groups and NS
+// activation stages (verify mode), OCC workgroups per compute unit (the register budget the compiler is held to).
+struct TileShape { int TN, TMW, WGN, WGM, NW, NS, OCC; };
+constexpr TileShape kShapes16[] = {     // verify mode (gemm_tile16w_kernel): TN, TMW count 32 x 32 tiles
+    {1, 4, 4, 1, 4, 2, 2},   // 0: 128 outputs x 128 tokens
+    {2, 2, 4, 1, 4, 4, 2},   // 1: 256 x 64, four activation stages
+    {1, 2, 4, 1, 4, 2, 3},   // 2: 128 x 64, three workgroups per compute unit
+    {1, 2, 4, 1, 4, 4, 2},   // 3: 128 x 64, four activation stages
 };
-constexpr int kFirstWide = 7;
-constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile_kernel)
-    {4, 8, 4, 1, 3, 2},   // 0: 256 outputs x 128 tokens
-    {4, 4, 2, 2, 3, 2},   // 1: 128 x 128
-    {4, 8, 2, 2, 3, 1},   // 2: 128 x 256
-    {2, 4, 4, 1, 3, 2},   // 3: 128 x 64
-    {4, 4, 4, 1, 3, 2},   // 4: 256 x 64
-    {2, 8, 4, 1, 3, 2},   // 5: 128 x 128, tall wave tiles
-    {3, 2, 1, 4, 3, 2},   // 6: 48 x 128
+constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile4w_kernel): TN, TMW count 32 x 32 tiles; NW = NS = 3
+    {1, 4, 4, 1, 3, 3, 2},   // 0: 128 x 128
+    {1, 2, 4, 1, 3, 3, 2},   // 1: 128 x 64
+    {1, 4, 2, 1, 3, 3, 2},   // 2: 64 x 128
+    {1, 2, 2, 1, 3, 3, 2},   // 3: 64 x 64
+    {1, 4, 4, 1, 3, 3, 1},   // 4: 128 x 128, one workgroup per compute unit
 };
-constexpr int kNumTileShapes = 7;
-constexpr int kNumShapes16 = 12;
+constexpr int kNumTileShapes = 5;
+constexpr int kNumShapes16 = 4;
 constexpr size_t kTicketBytes = 16384;                 // head of the workspace: arrival counters
 constexpr int kMaxTickets = (int)(kTicketBytes / 4);
 
@@ -175,11 +164,25 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
   TilePlan p{};
   int shape = 0, S = 1;
   if (!tile_override(w4a4, &shape, &S)) {
-    shape = M <= 64 ? 3 : 1;
+    // Measured on MI355X (sweeps over the Llama-shaped layers): the draft mode is bound
+    // by its per-group scaling arithmetic and does best on 128 x 64 blocks; the verify
+    // mode takes 128 x 128 blocks when they fill the chip at least twice over and
+    // 128 x 64 blocks (three workgroups per compute unit) otherwise.
+    if (w4a4) {
+      shape = 1;
+    } else {
+      const int blocks128 = ((N + 127) / 128) * ((M + 127) / 128);
+      shape = (M > 64 && blocks128 >= 2 * kNumCU) ? 0 : 2;
+    }
+    // K-slices until there are about 1.5 workgroups per compute unit, keeping at least
+    // eight groups per slice (the reduction costs one pass over S fp32 blocks)
+    const TileShape& t0 = shape_of(w4a4, shape);
+    const int blocks = ((N + 32 * t0.TN * t0.WGN - 1) / (32 * t0.TN * t0.WGN)) * ((M + 32 * t0.TMW * t0.WGM - 1) / (32 * t0.TMW * t0.WGM));
     S = 1;
+    while (S < 8 && blocks * S < 384 && G / (2 * S) >= 8) S *= 2;
   }
   const TileShape& t = shape_of(w4a4, shape);
-  const int edge = !w4a4 && shape >= kFirstWide ? 32 : 16;      // MFMA tile edge
+  const int edge = 32;                  // MFMA tile edge
   const int bn = edge * t.TN * t.WGN, bm = edge * t.TMW * t.WGM;
   p.shape = shape;
   p.nb = (N + bn - 1) / bn;
@@ -190,37 +193,24 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
   return p;
 }
 
-inline size_t plan_ws_bytes(const TilePlan& p, int M, int N) {
-  return p.S > 1 ? kTicketBytes + (size_t)p.S * M * N * 4 : 0;
+inline size_t plan_ws_bytes(bool w4a4, const TilePlan& p) {
+  if (p.S <= 1) return 0;
+  const TileShape& t = shape_of(w4a4, p.shape);
+  const int edge = 32;
+  const size_t block_floats = (size_t)(edge * t.TN * t.WGN) * (edge * t.TMW * t.WGM);   // whole blocks, ragged or not
+  return kTicketBytes + (size_t)p.S * p.nb * p.mb * block_floats * 4;
 }
 
-template <int TN, int TMW, int WGN, int WGM, int NW, int OCC>
-int launch_tile4_inst(const TileArgs& a, hipStream_t s) {
-  using C = TileCfg<true, TN, TMW, WGN, WGM>;
-  auto kern = gemm_tile_kernel<true, TN, TMW, WGN, WGM, OCC>;
-  if (C::kLdsBytes > 64 * 1024) {
-    static bool raised = false;       // the default cap on dynamic LDS is 64 KiB
-    if (!raised) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              C::kLdsBytes) != hipSuccess)
-        return QSPEC_ERR_HIP;
-      raised = true;
-    }
-  }
-  hipLaunchKernelGGL(kern, dim3(a.nb * a.mb * a.S), dim3(C::kThreads), C::kLdsBytes, s, a);
-  return QSPEC_OK;
-}
-
-template <int TN, int TMW, int WGN, int WGM, int NW, int OCC>
-int launch_tile16_inst(const TileArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL((gemm_tile16_kernel<TN, TMW, WGN, WGM, NW, OCC>), dim3(a.nb * a.mb * a.S),
+template <int PN, int PM, int WGN, int WGM, int OCC>
+int launch_tile4w_inst(const TileArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL((gemm_tile4w_kernel<PN, PM, WGN, WGM, OCC>), dim3(a.nb * a.mb * a.S),
                      dim3(64 * WGN * WGM), 0, s, a);
   return QSPEC_OK;
 }
 
-template <int PN, int PM, int WGN, int WGM, int NW, int OCC>
+template <int PN, int PM, int WGN, int WGM, int NW, int NS, int OCC>
 int launch_tile16w_inst(const TileArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL((gemm_tile16w_kernel<PN, PM, WGN, WGM, NW, OCC>), dim3(a.nb * a.mb * a.S),
+  hipLaunchKernelGGL((gemm_tile16w_kernel<PN, PM, WGN, WGM, NW, NS, OCC>), dim3(a.nb * a.mb * a.S),
                      dim3(64 * WGN * WGM), 0, s, a);
   return QSPEC_OK;
 }
@@ -232,28 +222,18 @@ int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s
   a.ws = plan.S > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kTicketBytes) : nullptr;
   if (W4A4) {
     switch (plan.shape) {
-      case 0: return launch_tile4_inst<4, 8, 4, 1, 3, 2>(a, s);
-      case 1: return launch_tile4_inst<4, 4, 2, 2, 3, 2>(a, s);
-      case 2: return launch_tile4_inst<4, 8, 2, 2, 3, 1>(a, s);
-      case 3: return launch_tile4_inst<2, 4, 4, 1, 3, 2>(a, s);
-      case 4: return launch_tile4_inst<4, 4, 4, 1, 3, 2>(a, s);
-      case 5: return launch_tile4_inst<2, 8, 4, 1, 3, 2>(a, s);
-      default: return launch_tile4_inst<3, 2, 1, 4, 3, 2>(a, s);
+      case 0: return launch_tile4w_inst<1, 4, 4, 1, 2>(a, s);
+      case 1: return launch_tile4w_inst<1, 2, 4, 1, 2>(a, s);
+      case 2: return launch_tile4w_inst<1, 4, 2, 1, 2>(a, s);
+      case 3: return launch_tile4w_inst<1, 2, 2, 1, 2>(a, s);
+      default: return launch_tile4w_inst<1, 4, 4, 1, 1>(a, s);
     }
   }
   switch (plan.shape) {
-    case 0: return launch_tile16_inst<4, 8, 4, 1, 2, 2>(a, s);
-    case 1: return launch_tile16_inst<2, 8, 4, 1, 4, 2>(a, s);
-    case 2: return launch_tile16_inst<4, 4, 2, 2, 2, 2>(a, s);
-    case 3: return launch_tile16_inst<2, 4, 4, 1, 4, 3>(a, s);
-    case 4: return launch_tile16_inst<4, 4, 4, 1, 2, 2>(a, s);
-    case 5: return launch_tile16_inst<3, 2, 1, 4, 4, 2>(a, s);
-    case 6: return launch_tile16_inst<4, 8, 4, 1, 4, 2>(a, s);
-    case 7: return launch_tile16w_inst<2, 4, 4, 1, 2, 2>(a, s);
-    case 8: return launch_tile16w_inst<2, 4, 4, 1, 4, 2>(a, s);
-    case 9: return launch_tile16w_inst<1, 4, 4, 1, 4, 2>(a, s);
-    case 10: return launch_tile16w_inst<2, 2, 4, 1, 4, 2>(a, s);
-    default: return launch_tile16w_inst<1, 2, 4, 1, 4, 3>(a, s);
+    case 0: return launch_tile16w_inst<1, 4, 4, 1, 4, 2, 2>(a, s);
+    case 1: return launch_tile16w_inst<2, 2, 4, 1, 4, 4, 2>(a, s);
+    case 2: return launch_tile16w_inst<1, 2, 4, 1, 4, 2, 3>(a, s);
+    default: return launch_tile16w_inst<1, 2, 4, 1, 4, 4, 2>(a, s);
   }
 }
 
@@ -284,8 +264,8 @@ size_t qspec_packed_weight_bytes(int N, int K, int group) {
 size_t qspec_workspace_bytes(int M, int N, int K, int group) {
   if (check_shape(M, N, K, group) != QSPEC_OK) return 0;
   if (use_stream(M) || use_generic()) return 0;
-  const size_t a = plan_ws_bytes(plan_tile(true, M, N, K), M, N);
-  const size_t b = plan_ws_bytes(plan_tile(false, M, N, K), M, N);
+  const size_t a = plan_ws_bytes(true, plan_tile(true, M, N, K));
+  const size_t b = plan_ws_bytes(false, plan_tile(false, M, N, K));
   return a > b ? a : b;
 }
 
@@ -441,9 +421,8 @@ int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* o
   } else {
     if (!use_generic()) {
       const TileShape& t = shape_of(mode_w4a4 != 0, plan_tile(mode_w4a4 != 0, M, N, K).shape);
-      if (mode_w4a4) snprintf(out, cap, "gemm_tile_kernel<true, %d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.OCC);
-      else snprintf(out, cap, "gemm_tile16%s_kernel<%d, %d, %d, %d, %d, %d>",
-                    plan_tile(false, M, N, K).shape >= kFirstWide ? "w" : "", t.TN, t.TMW, t.WGN, t.WGM, t.NW, t.OCC);
+      if (mode_w4a4) snprintf(out, cap, "gemm_tile4w_kernel<%d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.OCC);
+      else snprintf(out, cap, "gemm_tile16w_kernel<%d, %d, %d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.NW, t.NS, t.OCC);
     } else if (mode_w4a4) snprintf(out, cap, "gemm_w4a4_generic<%d, 4, false>", pick_tm(M));
     else snprintf(out, cap, "gemm_w4a16_generic<%d, 4>", pick_tm(M));
   }
