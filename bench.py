@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_PEAK_TFLOPS = {"w4a16": 2500.0, "w4a4": 5000.0}   # published dense fp16 / int8 matrix peaks
 
 
 def alg_bytes_w4a16(M, N, K):
@@ -48,7 +49,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--layers", type=int, default=32, help="decoder blocks with distinct weights per step")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="decoder blocks with distinct weights per step (default: 32 for configs 1-3, 8 for 4, 4 for 5; "
+                         "always far more packed weights than the 256 MB last-level cache holds)")
     ap.add_argument("--config", type=int, default=2, help="workload configuration (2 = headline)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -73,7 +76,7 @@ def main() -> int:
     cfg = synth.CONFIGS[args.config]
     Md, Mv = cfg.draft_M, cfg.verify_M
     lins = list(cfg.layers)
-    L = args.layers
+    L = args.layers or {4: 8, 5: 4}.get(args.config, 32)
     to = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
     # ---- inputs: block 0 from the seeded NumPy recipe, further blocks drawn on
@@ -213,7 +216,7 @@ def main() -> int:
     t_4 = time_runner(make_runner(run_w4a4), reps, 2)
     t_16d = time_runner(make_runner(run_w4a16_at_draft_M), reps, 2)
     calls = {}
-    kernels = {"quant_act_kernel": dict(launches=L * len(lins), seconds=t_q, flops=0,
+    kernels = {"quant_act_kernel": dict(launches=L * len(lins), seconds=t_q, flops=0, mode="quant",
                                         bytes=sum(alg_bytes_quant(Md, l.K) for l in lins) * L)}
     for i, lin in enumerate(lins):
         for kind, M, ab in (("w4a4", Md, alg_bytes_w4a4), ("w4a16", Mv, alg_bytes_w4a16)):
@@ -221,14 +224,16 @@ def main() -> int:
             calls[f"{lin.name}.{kind}.M{M}"] = dict(us=round(t / L * 1e6, 3),
                                                     TBps=round(ab(M, lin.N, lin.K) * L / t / 1e12, 3))
             name = B.describe_kernel(kind == "w4a4", M, lin.N, lin.K)          # the profiler's symbol
-            k = kernels.setdefault(name, dict(launches=0, seconds=0.0, bytes=0, flops=0))
+            k = kernels.setdefault(name, dict(launches=0, seconds=0.0, bytes=0, flops=0, mode=kind))
             k["launches"] += L
             k["seconds"] += t
             k["bytes"] += ab(M, lin.N, lin.K) * L
             k["flops"] += 2 * M * lin.N * lin.K * L
     dom = max(kernels, key=lambda k: kernels[k]["seconds"])
     kd = kernels[dom]
-    achieved = kd["bytes"] / kd["seconds"] / 1e9
+    # which roof bounds that kernel: the one its algorithmic work takes longer to reach
+    t_hbm = kd["bytes"] / (HBM_PEAK_GBS * 1e9)
+    t_mfma = kd["flops"] / (MFMA_PEAK_TFLOPS.get(kd["mode"], 1.0) * 1e12) if kd["flops"] else 0.0
     # HBM traffic per launch of that kernel from the committed counter summary (if it covers it)
     traffic = None
     try:
@@ -236,10 +241,19 @@ def main() -> int:
             traffic = json.load(f).get("bytes_per_launch", {}).get(dom)
     except (OSError, ValueError):
         pass
-    roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=traffic,
+    if t_mfma > t_hbm:
+        peak = MFMA_PEAK_TFLOPS[kd["mode"]]
+        achieved = kd["flops"] / kd["seconds"] / 1e12
+        roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 1), peak=peak,
+                        unit="TFLOP/s" if kd["mode"] == "w4a16" else "TOP/s")
+    else:
+        peak = HBM_PEAK_GBS
+        achieved = kd["bytes"] / kd["seconds"] / 1e9
+        roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=peak, unit="GB/s")
+    roofline.update(frac=round(achieved / peak, 4), traffic=traffic,
                     avg_launch_us=round(kd["seconds"] / kd["launches"] * 1e6, 3),
-                    alg_bytes_per_launch=kd["bytes"] // kd["launches"])
+                    alg_bytes_per_launch=kd["bytes"] // kd["launches"],
+                    alg_flops_per_launch=kd["flops"] // kd["launches"])
 
     # ---- CPU baseline: the oracle on one decoder block (bounded sample)
     cpu = None
@@ -287,7 +301,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "int4 weights; int8 MFMA/int32 (draft), fp16 MFMA/fp32 (verify)",
         "data": "synthetic",
-        "config": {"workload": f"config {args.config} ({cfg.label}): Llama-7B-shaped linears x {L} blocks, "
+        "config": {"workload": f"config {args.config} ({cfg.label}): Llama-shaped decoder linears x {L} blocks, "
                                f"draft W4A4 M={Md} (+quant_act), verify W4A16 M={Mv}",
                    "layers": L, "launch": "hip-graph" if use_graph else "eager",
                    "alg_bytes_per_step": bytes_step},

@@ -20,6 +20,7 @@
 // m % 16), k-block = lane / 16; D[i][j]: lane holds rows 4*(lane/16)+r.
 #pragma once
 #include "buffer.hpp"
+#include "exchange.hpp"
 #include "common.hpp"
 
 namespace qspec {
@@ -30,7 +31,10 @@ struct StreamArgs {
   const void* act;           // W4A4: qa bytes [M][K/2]; W4A16: x fp16 [M][K]
   const float* sa;           // W4A4: [M][G]
   uint16_t* y;               // fp16 [M][N]
+  float* ws;                 // S > 1: fp32 partial sums [S][tile block][output fragment]
+  unsigned* tickets;         // S > 1: one arrival counter per tile block, zero on entry and on exit
   int M, N, K, G;
+  int S;                     // K-slices: workgroup b owns tile block b / S, slice b % S
 };
 
 constexpr int kStreamWaves = 8;
@@ -162,11 +166,13 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r16 = lane & 15, kb = lane >> 4;
-  const int T0 = blockIdx.x * NT;
+  const int tb = blockIdx.x / p.S, slice = blockIdx.x - tb * p.S;
+  const int T0 = tb * NT;
   const int nt_valid = min(NT, p.N / 16 - T0);        // >= 1 by construction of the grid
   const int G = p.G;
-  // groups of this wave: wave, wave + W, ...  (n_g of them, possibly none)
-  const int n_g = (G - wave + W - 1) / W;
+  const int g0 = (int)(((long long)slice * G) / p.S), g1 = (int)(((long long)(slice + 1) * G) / p.S);
+  // groups of this wave: g0 + wave, g0 + wave + W, ...  (n_g of them, possibly none)
+  const int n_g = max(0, (g1 - g0 - wave + W - 1) / W);
 
   float facc[NT][TM][4];
 #pragma unroll
@@ -186,7 +192,7 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
     // Workgroups start at different points of their K sequence so that the 256
     // CUs do not all ask L2 for the same activation lines at the same moment.
     const int rot = (int)(blockIdx.x % (unsigned)n_g);
-    auto grp = [&](int it) { int q = it + rot; q = q >= n_g ? q - n_g : q; return wave + q * W; };
+    auto grp = [&](int it) { int q = it + rot; q = q >= n_g ? q - n_g : q; return g0 + wave + q * W; };
     // Two register sets alternate: the loads of the next group are in flight
     // while one group is computed.  (A third set was measured and is slower: the
     // memory system is throughput-bound here, more requests in flight only
@@ -215,6 +221,14 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
 #pragma unroll
       for (int r = 0; r < 4; ++r) red[wave][(j * TM + t) * 4 + r][lane] = facc[j][t][r];
   __syncthreads();
+  // With K-slices the sums go to the workspace first (one 16-byte piece per lane and
+  // output tile, contiguous per wavefront); the workgroup that arrives last at the
+  // tile block's counter adds the slices in slice order and stores fp16.
+  __shared__ unsigned ticket;
+  const int nblocks = gridDim.x / p.S;
+  auto frag = [&](int c, int o) -> float* {
+    return p.ws + ((((size_t)c * nblocks + tb) * (NT * TM) + o) * kWave + lane) * 4;
+  };
   for (int o = wave; o < NT * TM; o += W) {
     const int j = o / TM, t = o - j * TM;
     float s[4];
@@ -224,6 +238,30 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
 #pragma unroll
       for (int w = 0; w < W; ++w) v += red[w][o * 4 + r][lane];
       s[r] = v;
+    }
+    if (p.S > 1) {
+      float* f = frag(slice, o);
+      store_shared_f2(f, s[0], s[1]);
+      store_shared_f2(f + 2, s[2], s[3]);
+      continue;
+    }
+    const int m = 16 * t + r16;
+    if (j < nt_valid && m < p.M) {
+      uint2 out;
+      out.x = (uint32_t)float_to_half_bits(s[0]) | ((uint32_t)float_to_half_bits(s[1]) << 16);
+      out.y = (uint32_t)float_to_half_bits(s[2]) | ((uint32_t)float_to_half_bits(s[3]) << 16);
+      *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + (T0 + j) * 16 + 4 * kb) = out;
+    }
+  }
+  if (p.S == 1) return;
+  if (!last_arrival(p.tickets, p.S, (unsigned)tb, &ticket)) return;
+  for (int o = wave; o < NT * TM; o += W) {
+    const int j = o / TM, t = o - j * TM;
+    float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int c = 0; c < p.S; ++c) {            // fixed order: the result does not depend on who came last
+      const float* f = frag(c, o);
+      const float2 a = load_shared_f2(f), b = load_shared_f2(f + 2);
+      s[0] += a.x; s[1] += a.y; s[2] += b.x; s[3] += b.y;
     }
     const int m = 16 * t + r16;
     if (j < nt_valid && m < p.M) {

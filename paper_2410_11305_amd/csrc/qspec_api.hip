@@ -81,42 +81,78 @@ bool use_generic() {
 // ---------------------------------------------------------------- streaming (small-M) kernel
 constexpr int kStreamMaxM = 32;
 
-// n-tiles per workgroup: minimise rounds x work per round over the 256 CUs, prefer
-// the larger NT on a tie (the activation operand is re-used NT times).
-// QSPEC_STREAM_NT=1..4 overrides (benchmark A/B only).
-int stream_nt(int N) {
-  const int tiles = N / 16;
-  if (const char* e = getenv("QSPEC_STREAM_NT")) {
-    const int v = atoi(e);
-    if (v >= 1 && v <= 4) return v;
+constexpr size_t kTicketBytes = 16384;                 // head of the workspace: arrival counters
+constexpr int kMaxTickets = (int)(kTicketBytes / 4);
+
+// Plan of the streaming kernel: NT adjacent n-tiles per workgroup, S K-slices.
+// A pure function of (mode, M, N, K), so that qspec_workspace_bytes and the GEMM
+// entry points agree.  QSPEC_STREAM_W4A4 / QSPEC_STREAM_W4A16 = "NT,S" override the
+// heuristic (benchmark A/B only).
+struct StreamPlan { int nt, S, blocks; };
+constexpr int kStreamNts[] = {1, 2, 3, 4, 6};
+
+StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
+  const int tiles = N / 16, G = K / kGroup;
+  StreamPlan p{1, 1, tiles};
+  int nt = 0, S = 0;
+  const char* e = getenv(w4a4 ? "QSPEC_STREAM_W4A4" : "QSPEC_STREAM_W4A16");
+  bool forced = e && sscanf(e, "%d,%d", &nt, &S) == 2 && S >= 1 && S <= G;
+  if (forced) {
+    forced = false;
+    for (int v : kStreamNts) forced = forced || v == nt;
   }
-  int best = 1, best_cost = 1 << 30;
-  for (int nt = 1; nt <= 4; ++nt) {
-    const int blocks = (tiles + nt - 1) / nt;
-    const int cost = ((blocks + kNumCU - 1) / kNumCU) * nt;
-    if (cost <= best_cost) { best_cost = cost; best = nt; }
+  if (!forced) {
+    // Cost of a plan, in units of one weight tile (1 KB from HBM) per wavefront:
+    // rounds over the 256 compute units x groups per wavefront x (NT weight tiles +
+    // the activation operand of the group, which comes from L2 and is re-used for
+    // the NT tiles).  K-slices are never chosen here: measured on MI355X, the
+    // exchange (write-through stores, a ticket, S dependent trips to memory) costs
+    // 4 to 10 us, more than any of these launches saves; the path stays available
+    // to the override and is covered by the tests.
+    const int tm = M <= 16 ? 1 : 2;
+    const double act = w4a4 ? 0.4 * tm : 1.6 * tm;
+    double best = 1e30;
+    for (int s = 1; s <= 1; s *= 2) {
+      for (int v : kStreamNts) {
+        const int blocks = (tiles + v - 1) / v;
+        if (s > 1 && blocks > kMaxTickets) continue;
+        const int rounds = (blocks * s + kNumCU - 1) / kNumCU;
+        const int per_wave = ((G + s - 1) / s + kStreamWaves - 1) / kStreamWaves;
+        const double cost = rounds * (per_wave * (v + act) + (s > 1 ? 0.25 * s * v * tm + 2.0 : 0.0));
+        if (cost < best - 1e-9 || (cost < best + 1e-9 && v > nt)) { best = cost; nt = v; S = s; }
+      }
+    }
   }
-  return best;
+  p.nt = nt; p.S = S; p.blocks = (tiles + nt - 1) / nt;
+  return p;
+}
+
+inline size_t stream_ws_bytes(const StreamPlan& p, int M) {
+  const int tm = M <= 16 ? 1 : 2;
+  return p.S > 1 ? kTicketBytes + (size_t)p.S * p.blocks * p.nt * tm * 1024 : 0;
 }
 
 bool use_stream(int M) { return M <= kStreamMaxM; }
 
 template <bool W4A4, int TM>
-void launch_stream_tm(const StreamArgs& a, int nt, hipStream_t s) {
-  const int tiles = a.N / 16;
-  dim3 grid((tiles + nt - 1) / nt), block(kStreamWaves * 64);
-  switch (nt) {
+void launch_stream_tm(const StreamArgs& a, const StreamPlan& plan, hipStream_t s) {
+  dim3 grid(plan.blocks * plan.S), block(kStreamWaves * 64);
+  switch (plan.nt) {
     case 1: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 1>), grid, block, 0, s, a); break;
     case 2: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 2>), grid, block, 0, s, a); break;
     case 3: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 3>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 4>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 4>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 6>), grid, block, 0, s, a); break;
   }
 }
 
 template <bool W4A4>
-void launch_stream(const StreamArgs& a, hipStream_t s) {
-  const int nt = stream_nt(a.N);
-  if (a.M <= 16) launch_stream_tm<W4A4, 1>(a, nt, s); else launch_stream_tm<W4A4, 2>(a, nt, s);
+void launch_stream(StreamArgs a, void* workspace, hipStream_t s) {
+  const StreamPlan plan = plan_stream(W4A4, a.M, a.N, a.K);
+  a.S = plan.S;
+  a.tickets = static_cast<unsigned*>(workspace);
+  a.ws = plan.S > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kTicketBytes) : nullptr;
+  if (a.M <= 16) launch_stream_tm<W4A4, 1>(a, plan, s); else launch_stream_tm<W4A4, 2>(a, plan, s);
 }
 
 // ---------------------------------------------------------------- tiled (M > 32) kernels
@@ -139,9 +175,6 @@ constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile4w_kernel): TN, 
 };
 constexpr int kNumTileShapes = 5;
 constexpr int kNumShapes16 = 4;
-constexpr size_t kTicketBytes = 16384;                 // head of the workspace: arrival counters
-constexpr int kMaxTickets = (int)(kTicketBytes / 4);
-
 struct TilePlan {
   int shape;      // index into the mode's shape table
   int S;          // K-slices
@@ -263,7 +296,12 @@ size_t qspec_packed_weight_bytes(int N, int K, int group) {
 
 size_t qspec_workspace_bytes(int M, int N, int K, int group) {
   if (check_shape(M, N, K, group) != QSPEC_OK) return 0;
-  if (use_stream(M) || use_generic()) return 0;
+  if (use_stream(M)) {
+    const size_t a = stream_ws_bytes(plan_stream(true, M, N, K), M);
+    const size_t b = stream_ws_bytes(plan_stream(false, M, N, K), M);
+    return a > b ? a : b;
+  }
+  if (use_generic()) return 0;
   const size_t a = plan_ws_bytes(true, plan_tile(true, M, N, K));
   const size_t b = plan_ws_bytes(false, plan_tile(false, M, N, K));
   return a > b ? a : b;
@@ -335,7 +373,7 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int 
     StreamArgs st{};
     st.codes = a.codes; st.scalesT = a.scalesT; st.act = qa; st.sa = sa; st.y = a.y;
     st.M = M; st.N = N; st.K = K; st.G = a.G;
-    launch_stream<true>(st, s);
+    launch_stream<true>(st, workspace, s);
     return launch_status();
   }
   if (!use_generic()) {
@@ -373,7 +411,7 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16, int M, int N, int K,
     StreamArgs st{};
     st.codes = a.codes; st.scalesT = a.scalesT; st.act = x_f16; st.y = a.y;
     st.M = M; st.N = N; st.K = K; st.G = a.G;
-    launch_stream<false>(st, s);
+    launch_stream<false>(st, workspace, s);
     return launch_status();
   }
   if (!use_generic()) {
@@ -417,7 +455,7 @@ int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* o
   if (int st = check_shape(M, N, K, group)) return st;
   const char* b = mode_w4a4 ? "true" : "false";
   if (use_stream(M)) {
-    snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, M <= 16 ? 1 : 2, stream_nt(N));
+    snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, M <= 16 ? 1 : 2, plan_stream(mode_w4a4 != 0, M, N, K).nt);
   } else {
     if (!use_generic()) {
       const TileShape& t = shape_of(mode_w4a4 != 0, plan_tile(mode_w4a4 != 0, M, N, K).shape);

@@ -9,6 +9,7 @@
 #pragma once
 #include "buffer.hpp"
 #include "common.hpp"
+#include "exchange.hpp"
 
 #include <type_traits>
 
@@ -66,19 +67,6 @@ __device__ inline uint32_t word_of(const uint4& q, int i) {
   return i == 0 ? q.x : i == 1 ? q.y : i == 2 ? q.z : q.w;
 }
 
-// Partial sums that several workgroups exchange inside one launch go past the
-// per-XCD L2 caches (which are not coherent with each other): device-scope
-// relaxed atomic accesses compile to write-through stores and cache-bypassing
-// loads.  That is much cheaper than device-scope fences, each of which writes
-// back and invalidates a whole L2.
-__device__ __forceinline__ void store_shared_f2(float* p, float a, float b) {
-  const uint64_t v = (uint64_t)__builtin_bit_cast(uint32_t, a) | ((uint64_t)__builtin_bit_cast(uint32_t, b) << 32);
-  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float2 load_shared_f2(const float* p) {
-  const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return float2{__builtin_bit_cast(float, (uint32_t)v), __builtin_bit_cast(float, (uint32_t)(v >> 32))};
-}
 // The partial sums of K-slice c of output block blk: the workgroup's accumulator
 // registers in register-pair-major, thread-minor order (pair q of thread t at float
 // 2*(q*threads + t)), so that every wave-wide store or load is one contiguous run
@@ -86,21 +74,6 @@ __device__ __forceinline__ float2 load_shared_f2(const float* p) {
 __device__ __forceinline__ float* slice_frag(const TileArgs& p, int c, unsigned blk, int floats_per_block) {
   return p.ws + ((size_t)c * (p.nb * p.mb) + blk) * (size_t)floats_per_block;
 }
-// Take a ticket of output block blk once every store of this workgroup has been
-// performed; true for the workgroup that arrives last of S (it also puts the
-// counter back to zero for the next launch).
-__device__ __forceinline__ bool last_arrival(const TileArgs& p, unsigned blk, unsigned* ticket_lds) {
-  __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's write-through stores have been performed
-  __syncthreads();                      // ... and those of the whole workgroup
-  if (threadIdx.x == 0) {
-    const unsigned old = atomicAdd(&p.tickets[blk], 1u);
-    if (old == (unsigned)p.S - 1) atomicExch(&p.tickets[blk], 0u);
-    *ticket_lds = old;
-  }
-  __syncthreads();
-  return *ticket_lds == (unsigned)p.S - 1;
-}
-
 // Output of a wave's PN x PM tiles of 32 x 32 (first output feature n0, first token
 // row mrow0).  MFMA D layout: lane l holds column m = l % 32 and rows 8a + 4h + r
 // (h = l / 32; a, r = 0..3) in register 4a + r, i.e. four runs of four consecutive
@@ -142,7 +115,7 @@ __device__ __forceinline__ void tile_store32(const TileArgs& p, const TileCoord&
       for (int e = 0; e < 8; ++e)
         store_shared_f2(mine + 2 * (((j * PM + t) * 8 + e) * nthr + tid), acc[j][t][2 * e], acc[j][t][2 * e + 1]);
   __shared__ unsigned ticket32;
-  if (!last_arrival(p, blk, &ticket32)) return;
+  if (!last_arrival(p.tickets, p.S, blk, &ticket32)) return;
   // Add the slices in the fixed order 0 .. S-1 whoever arrives last (its own slice is
   // read back like the others), so the result does not depend on timing.  The loads
   // bypass the caches and each costs a trip to memory: sixteen are kept in flight.

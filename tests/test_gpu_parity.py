@@ -225,6 +225,35 @@ def test_tile_kernels_every_workgroup_shape(env, monkeypatch, shape, S):
         assert int(ws[:16384].count_nonzero()) == 0
 
 
+@pytest.mark.parametrize("plan", ["1,2", "3,4", "6,2", "4,1", "6,1"])
+@pytest.mark.parametrize("M", [5, 16, 29])
+def test_stream_kernels_with_k_slices(env, monkeypatch, M, plan):
+    """Streaming (M <= 32) kernels with every tile count, alone and with K-slices
+    that meet in the workspace; 11 groups do not divide by the slice count and the
+    last tile block is ragged."""
+    torch, B = env
+    N, K = 400, 1408
+    monkeypatch.setenv("QSPEC_STREAM_W4A4", plan)
+    monkeypatch.setenv("QSPEC_STREAM_W4A16", plan)
+    codes, scales, x = synth.generic_case(700 + M, M, N, K)
+    blob = B.pack_weights(dev(torch, codes), dev(torch, scales))
+    qa, sa, q_ref, s_ref = _check_quant(torch, B, x)
+    ws = B.alloc_workspace(B.workspace_bytes(M, N, K))
+    ref4 = orc.gemm_w4a4(q_ref, s_ref, codes, scales)
+    ref16 = orc.gemm_w4a16(x, codes, scales)
+    xd = dev(torch, x)
+    outs = []
+    for _ in range(2):
+        y4 = B.gemm_w4a4(blob, qa, sa, N, workspace=ws)
+        y16 = B.gemm_w4a16(blob, xd, N, workspace=ws)
+        torch.cuda.synchronize()
+        assert rel_err(y4.cpu().numpy(), ref4) <= TOL
+        assert rel_err(y16.cpu().numpy(), ref16) <= TOL
+        outs.append((y4, y16))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert int(ws[:16384].count_nonzero()) == 0
+
+
 def test_tile_kernel_exact_cases(env, monkeypatch):
     """Exactly representable products through the tiled kernels with K-slices:
     any summation order must give the oracle's bits."""
