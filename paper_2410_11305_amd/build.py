@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -12,10 +13,32 @@ SOURCES = [os.path.join(HERE, "csrc", "qspec_api.hip")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    # per-kernel register / spill report, read back below
+    "-Rpass-analysis=kernel-resource-usage",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
+
+
+# gemm_tile16w_kernel orders its waits on direct-to-LDS loads by counting the loads
+# issued after them; a register spill would put stores into that sequence (stores
+# complete out of order with loads), so such an instance must not be shipped.
+NO_SPILL_KERNELS = ("gemm_tile16w_kernel",)
+
+
+def spilling_kernels(report: str, names) -> list:
+    """Mangled names of kernels matching `names` whose resource remarks show VGPR spills."""
+    bad, current = [], None
+    for line in report.splitlines():
+        m = re.search(r"remark: +Function Name: (\S+)", line)
+        if m:
+            current = m.group(1)
+            continue
+        m = re.search(r"remark: +VGPRs Spill: (\d+)", line)
+        if m and current and int(m.group(1)) > 0 and any(n in current for n in names):
+            bad.append(current)
+    return bad
 
 
 def hipcc() -> str:
@@ -32,11 +55,15 @@ def build(verbose: bool = True) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    out = "\n".join(l for l in res.stdout.splitlines()
+                    if "packed-fp32-ops" not in l and "-Rpass-analysis=kernel-resource-usage" not in l)
     if verbose and out.strip():
         print(out, flush=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + out)
+    spilled = spilling_kernels(res.stdout, NO_SPILL_KERNELS)
+    if spilled:
+        raise RuntimeError("kernels that must not spill registers do: " + ", ".join(spilled))
     return LIB_PATH
 
 

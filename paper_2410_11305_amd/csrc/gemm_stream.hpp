@@ -93,25 +93,29 @@ template <bool W4A4, int TM, int NT>
 __device__ inline void compute_group(const GroupRegs<W4A4, TM, NT>& R, float (&facc)[NT][TM][4], uint8_t* xbuf,
                                      int lane) {
   if (W4A4) {
-    I8Pair b[TM];
-#pragma unroll
-    for (int t = 0; t < TM; ++t) b[t] = unpack_i8(R.a[t]);
+    // weight operands and scales of all NT tiles first, then token tile by token tile
+    // (one unpacked activation operand live at a time: TM goes up to 8)
+    I8Pair a[NT];
+    float sw[NT][4];
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
-      const I8Pair a = unpack_i8(R.w[j]);
-      float sw[4];
+      a[j] = unpack_i8(R.w[j]);
       // both int8 operands carry a factor 16: fold 2^-8 into the weight scale (exact)
-      sw[0] = half_bits_to_float((uint16_t)(R.sw[j].x & 0xFFFF)) * 0.00390625f;
-      sw[1] = half_bits_to_float((uint16_t)(R.sw[j].x >> 16)) * 0.00390625f;
-      sw[2] = half_bits_to_float((uint16_t)(R.sw[j].y & 0xFFFF)) * 0.00390625f;
-      sw[3] = half_bits_to_float((uint16_t)(R.sw[j].y >> 16)) * 0.00390625f;
+      sw[j][0] = half_bits_to_float((uint16_t)(R.sw[j].x & 0xFFFF)) * 0.00390625f;
+      sw[j][1] = half_bits_to_float((uint16_t)(R.sw[j].x >> 16)) * 0.00390625f;
+      sw[j][2] = half_bits_to_float((uint16_t)(R.sw[j].y & 0xFFFF)) * 0.00390625f;
+      sw[j][3] = half_bits_to_float((uint16_t)(R.sw[j].y >> 16)) * 0.00390625f;
+    }
 #pragma unroll
-      for (int t = 0; t < TM; ++t) {
+    for (int t = 0; t < TM; ++t) {
+      const I8Pair b = unpack_i8(R.a[t]);
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
         v4i acc = {0, 0, 0, 0};
-        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a.lo, b[t].lo, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a.hi, b[t].hi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[j].lo, b.lo, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[j].hi, b.hi, acc, 0, 0, 0);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) facc[j][t][r] += (float)acc[r] * (R.sa[t] * sw[r]);
+        for (int r = 0; r < 4; ++r) facc[j][t][r] += (float)acc[r] * (R.sa[t] * sw[j][r]);
       }
     }
   } else {
@@ -158,10 +162,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
   constexpr int W = kStreamWaves;
   // LDS: per-wave transpose buffers while streaming (verify mode), re-used as the
   // split-K reduction buffer at the end
-  constexpr int kRedBytes = W * NT * TM * 4 * kWave * 4;
+  constexpr int kChunk = NT * TM < W ? NT * TM : W;      // output tiles combined per pass, one per wave
+  constexpr int kRedBytes = W * kChunk * 4 * kWave * 4;
   constexpr int kXBytes = W4A4 ? 0 : W * TM * 16 * kXPitch;
   __shared__ __attribute__((aligned(16))) uint8_t lds[kRedBytes > kXBytes ? kRedBytes : kXBytes];
-  float (*red)[NT * TM * 4][kWave] = reinterpret_cast<float (*)[NT * TM * 4][kWave]>(lds);
+  float (*red)[kChunk * 4][kWave] = reinterpret_cast<float (*)[kChunk * 4][kWave]>(lds);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -212,45 +217,52 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
     }
   }
 
-  // ---- combine the eight K-slices of every output tile
-  __syncthreads();               // the transpose buffers are dead from here on
-#pragma unroll
-  for (int j = 0; j < NT; ++j)
-#pragma unroll
-    for (int t = 0; t < TM; ++t)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) red[wave][(j * TM + t) * 4 + r][lane] = facc[j][t][r];
-  __syncthreads();
-  // With K-slices the sums go to the workspace first (one 16-byte piece per lane and
-  // output tile, contiguous per wavefront); the workgroup that arrives last at the
-  // tile block's counter adds the slices in slice order and stores fp16.
+  // ---- combine the eight per-wave sums of every output tile, kChunk tiles per pass
+  // through LDS (the transpose buffers are dead from here on).  With K-slices the
+  // sums go to the workspace first (one 16-byte piece per lane and output tile,
+  // contiguous per wavefront); the workgroup that arrives last at the tile block's
+  // counter adds the slices in slice order and stores fp16.
   __shared__ unsigned ticket;
   const int nblocks = gridDim.x / p.S;
   auto frag = [&](int c, int o) -> float* {
     return p.ws + ((((size_t)c * nblocks + tb) * (NT * TM) + o) * kWave + lane) * 4;
   };
-  for (int o = wave; o < NT * TM; o += W) {
-    const int j = o / TM, t = o - j * TM;
-    float s[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float v = 0.0f;
+  for (int base = 0; base < NT * TM; base += kChunk) {
+    __syncthreads();
 #pragma unroll
-      for (int w = 0; w < W; ++w) v += red[w][o * 4 + r][lane];
-      s[r] = v;
+    for (int c = 0; c < kChunk; ++c) {
+      const int o = base + c;                      // compile-time: facc stays in registers
+      if (o < NT * TM) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave][c * 4 + r][lane] = facc[o / TM][o % TM][r];
+      }
     }
-    if (p.S > 1) {
-      float* f = frag(slice, o);
-      store_shared_f2(f, s[0], s[1]);
-      store_shared_f2(f + 2, s[2], s[3]);
-      continue;
-    }
-    const int m = 16 * t + r16;
-    if (j < nt_valid && m < p.M) {
-      uint2 out;
-      out.x = (uint32_t)float_to_half_bits(s[0]) | ((uint32_t)float_to_half_bits(s[1]) << 16);
-      out.y = (uint32_t)float_to_half_bits(s[2]) | ((uint32_t)float_to_half_bits(s[3]) << 16);
-      *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + (T0 + j) * 16 + 4 * kb) = out;
+    __syncthreads();
+    const int o = base + wave;
+    if (wave < kChunk && o < NT * TM) {
+      const int j = o / TM, t = o - j * TM;
+      float s[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < W; ++w) v += red[w][wave * 4 + r][lane];
+        s[r] = v;
+      }
+      if (p.S > 1) {
+        float* f = frag(slice, o);
+        store_shared_f2(f, s[0], s[1]);
+        store_shared_f2(f + 2, s[2], s[3]);
+      } else {
+        const int m = 16 * t + r16;
+        if (j < nt_valid && m < p.M) {
+          uint2 out;
+          out.x = (uint32_t)float_to_half_bits(s[0]) | ((uint32_t)float_to_half_bits(s[1]) << 16);
+          out.y = (uint32_t)float_to_half_bits(s[2]) | ((uint32_t)float_to_half_bits(s[3]) << 16);
+          *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + (T0 + j) * 16 + 4 * kb) = out;
+        }
+      }
     }
   }
   if (p.S == 1) return;

@@ -79,13 +79,13 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile16w_kernel(TileA
   const rsrc_t r_codes = make_rsrc(p.codes, (uint32_t)((size_t)p.N * p.K / 2));
   const rsrc_t r_scales = make_rsrc(p.scalesT, (uint32_t)((size_t)p.N * G * 2));
   const rsrc_t r_act = make_rsrc(p.act, (uint32_t)((size_t)p.M * p.K * 2));
-  // The groups of the slice are visited in rotated order, q = 0 .. ng-1 -> group
-  // g0 + (q + rot) % ng, with a different rot per workgroup: workgroups that start
-  // together would otherwise ask the L2 for the same activation lines (one channel)
-  // at the same moment, group after group.
+  // Every workgroup walks its K groups in the same order, q = 0 .. ng-1 -> group g0 + q:
+  // the workgroups of an XCD then need the same narrow window of activation columns at
+  // about the same time and find it in their L2.  (Starting each weight stripe at a
+  // different group was measured: no faster, and 9x the algorithmic bytes fetched,
+  // because the whole activation matrix then has to live in a 4 MB L2.)
   const int ng = g1 - g0;
-  const int rot = (int)(((unsigned)tc.nblk * 5u) % (unsigned)ng);     // one rot per weight stripe: its m-blocks stay in step
-  auto group_of = [&](int q) -> int { const int r = q + rot; return g0 + (r >= ng ? r - ng : r); };
+  auto group_of = [&](int q) -> int { return g0 + q; };
   auto past_end = [&](int q) -> uint32_t { return (uint32_t)((ng - 1 - q) >> 31) << 31; };   // q >= ng ? bit 31 : 0
 
   // ---- activations: global -> LDS.  Transfer u of this wave fills block q = wave +

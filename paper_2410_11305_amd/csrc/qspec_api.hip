@@ -80,6 +80,7 @@ bool use_generic() {
 
 // ---------------------------------------------------------------- streaming (small-M) kernel
 constexpr int kStreamMaxM = 32;
+constexpr int kStreamMaxM4 = 64;
 
 constexpr size_t kTicketBytes = 16384;                 // head of the workspace: arrival counters
 constexpr int kMaxTickets = (int)(kTicketBytes / 4);
@@ -89,6 +90,7 @@ constexpr int kMaxTickets = (int)(kTicketBytes / 4);
 // entry points agree.  QSPEC_STREAM_W4A4 / QSPEC_STREAM_W4A16 = "NT,S" override the
 // heuristic (benchmark A/B only).
 struct StreamPlan { int nt, S, blocks; };
+inline int stream_tm(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8; }   // 16-token tiles per workgroup
 constexpr int kStreamNts[] = {1, 2, 3, 4, 6};
 
 StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
@@ -99,7 +101,7 @@ StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
   bool forced = e && sscanf(e, "%d,%d", &nt, &S) == 2 && S >= 1 && S <= G;
   if (forced) {
     forced = false;
-    for (int v : kStreamNts) forced = forced || v == nt;
+    for (int v : kStreamNts) forced = forced || (v == nt && v * stream_tm(M) <= 16);
   }
   if (!forced) {
     // Cost of a plan, in units of one weight tile (1 KB from HBM) per wavefront:
@@ -109,11 +111,12 @@ StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
     // exchange (write-through stores, a ticket, S dependent trips to memory) costs
     // 4 to 10 us, more than any of these launches saves; the path stays available
     // to the override and is covered by the tests.
-    const int tm = M <= 16 ? 1 : 2;
+    const int tm = stream_tm(M);
     const double act = w4a4 ? 0.4 * tm : 1.6 * tm;
     double best = 1e30;
     for (int s = 1; s <= 1; s *= 2) {
       for (int v : kStreamNts) {
+        if (v * tm > 16) continue;                        // 4 accumulator registers per tile pair; beyond 64 the kernel spills
         const int blocks = (tiles + v - 1) / v;
         if (s > 1 && blocks > kMaxTickets) continue;
         const int rounds = (blocks * s + kNumCU - 1) / kNumCU;
@@ -128,11 +131,20 @@ StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
 }
 
 inline size_t stream_ws_bytes(const StreamPlan& p, int M) {
-  const int tm = M <= 16 ? 1 : 2;
+  const int tm = stream_tm(M);
   return p.S > 1 ? kTicketBytes + (size_t)p.S * p.blocks * p.nt * tm * 1024 : 0;
 }
 
-bool use_stream(int M) { return M <= kStreamMaxM; }
+// The draft mode streams up to 64 tokens (its activation operand is a quarter of
+// the verify mode's); QSPEC_STREAM_MAX_W4A4 overrides that bound (benchmark A/B only).
+bool use_stream(bool w4a4, int M) {
+  int max_m = w4a4 ? kStreamMaxM4 : kStreamMaxM;
+  if (w4a4) {
+    // measured: beyond 64 tokens the tiled kernel wins
+    if (const char* e = getenv("QSPEC_STREAM_MAX_W4A4")) { const int v = atoi(e); if (v >= 32 && v <= 128) max_m = v; }
+  }
+  return M <= max_m;
+}
 
 template <bool W4A4, int TM>
 void launch_stream_tm(const StreamArgs& a, const StreamPlan& plan, hipStream_t s) {
@@ -140,9 +152,9 @@ void launch_stream_tm(const StreamArgs& a, const StreamPlan& plan, hipStream_t s
   switch (plan.nt) {
     case 1: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 1>), grid, block, 0, s, a); break;
     case 2: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 2>), grid, block, 0, s, a); break;
-    case 3: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 3>), grid, block, 0, s, a); break;
-    case 4: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 4>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 6>), grid, block, 0, s, a); break;
+    case 3: if constexpr (TM <= 4) hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 3>), grid, block, 0, s, a); break;
+    case 4: if constexpr (TM <= 4) hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 4>), grid, block, 0, s, a); break;
+    default: if constexpr (TM <= 2) hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 6>), grid, block, 0, s, a); break;
   }
 }
 
@@ -152,7 +164,12 @@ void launch_stream(StreamArgs a, void* workspace, hipStream_t s) {
   a.S = plan.S;
   a.tickets = static_cast<unsigned*>(workspace);
   a.ws = plan.S > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kTicketBytes) : nullptr;
-  if (a.M <= 16) launch_stream_tm<W4A4, 1>(a, plan, s); else launch_stream_tm<W4A4, 2>(a, plan, s);
+  switch (stream_tm(a.M)) {
+    case 1: launch_stream_tm<W4A4, 1>(a, plan, s); break;
+    case 2: launch_stream_tm<W4A4, 2>(a, plan, s); break;
+    case 4: if constexpr (W4A4) launch_stream_tm<true, 4>(a, plan, s); break;
+    default: if constexpr (W4A4) launch_stream_tm<true, 8>(a, plan, s); break;
+  }
 }
 
 // ---------------------------------------------------------------- tiled (M > 32) kernels
@@ -296,15 +313,14 @@ size_t qspec_packed_weight_bytes(int N, int K, int group) {
 
 size_t qspec_workspace_bytes(int M, int N, int K, int group) {
   if (check_shape(M, N, K, group) != QSPEC_OK) return 0;
-  if (use_stream(M)) {
-    const size_t a = stream_ws_bytes(plan_stream(true, M, N, K), M);
-    const size_t b = stream_ws_bytes(plan_stream(false, M, N, K), M);
-    return a > b ? a : b;
+  // the larger of what the two modes need for this shape
+  size_t need[2];
+  for (int w4a4 = 0; w4a4 < 2; ++w4a4) {
+    if (use_stream(w4a4 != 0, M)) need[w4a4] = stream_ws_bytes(plan_stream(w4a4 != 0, M, N, K), M);
+    else if (use_generic()) need[w4a4] = 0;
+    else need[w4a4] = plan_ws_bytes(w4a4 != 0, plan_tile(w4a4 != 0, M, N, K));
   }
-  if (use_generic()) return 0;
-  const size_t a = plan_ws_bytes(true, plan_tile(true, M, N, K));
-  const size_t b = plan_ws_bytes(false, plan_tile(false, M, N, K));
-  return a > b ? a : b;
+  return need[0] > need[1] ? need[0] : need[1];
 }
 
 int qspec_pack_weights(const int8_t* codes, const void* scales_f16, int N, int K, int group,
@@ -369,7 +385,7 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int 
   a.y = static_cast<uint16_t*>(y_f16);
   a.M = M; a.N = N; a.K = K; a.G = K / kGroup;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (use_stream(M)) {
+  if (use_stream(true, M)) {
     StreamArgs st{};
     st.codes = a.codes; st.scalesT = a.scalesT; st.act = qa; st.sa = sa; st.y = a.y;
     st.M = M; st.N = N; st.K = K; st.G = a.G;
@@ -407,7 +423,7 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16, int M, int N, int K,
   a.y = static_cast<uint16_t*>(y_f16);
   a.M = M; a.N = N; a.K = K; a.G = K / kGroup;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (use_stream(M)) {
+  if (use_stream(false, M)) {
     StreamArgs st{};
     st.codes = a.codes; st.scalesT = a.scalesT; st.act = x_f16; st.y = a.y;
     st.M = M; st.N = N; st.K = K; st.G = a.G;
@@ -454,8 +470,8 @@ int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* o
   if (!out || cap == 0) return QSPEC_ERR_NULL;
   if (int st = check_shape(M, N, K, group)) return st;
   const char* b = mode_w4a4 ? "true" : "false";
-  if (use_stream(M)) {
-    snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, M <= 16 ? 1 : 2, plan_stream(mode_w4a4 != 0, M, N, K).nt);
+  if (use_stream(mode_w4a4 != 0, M)) {
+    snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, stream_tm(M), plan_stream(mode_w4a4 != 0, M, N, K).nt);
   } else {
     if (!use_generic()) {
       const TileShape& t = shape_of(mode_w4a4 != 0, plan_tile(mode_w4a4 != 0, M, N, K).shape);

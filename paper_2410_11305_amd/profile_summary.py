@@ -10,6 +10,7 @@ The counters are scaled by what they read for the one plain 256 MiB device
 copy that bench.py issues before its timed region (__amd_rocclr_copyBuffer).
 
 usage: python -m paper_2410_11305_amd.profile_summary <in_dir> <out_dir> [tag]
+(the digits in the tag name the bench.py --config the runs were made with)
 """
 from __future__ import annotations
 
@@ -21,9 +22,9 @@ import sys
 
 CAL_BYTES = 256 << 20
 CMD_KT = ("rocprofv3 --kernel-trace --stats -f csv -d <dir> -o kt -- "
-          "python3 bench.py --steps 5 --warmup 1 --no-cpu-baseline")
+          "python3 bench.py --config {cfg} --steps 5 --warmup 1 --no-cpu-baseline")
 CMD_PMC = ("rocprofv3 --pmc {c} -f csv -d <dir> -o {o} -- "
-           "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --no-graph")
+           "python3 bench.py --config {cfg} --steps 2 --warmup 1 --no-cpu-baseline --no-graph")
 
 
 def _short(name: str) -> str:
@@ -41,8 +42,9 @@ def _counter_means(path):
 
 def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
     os.makedirs(out_dir, exist_ok=True)
+    cfg = "".join(ch for ch in tag if ch.isdigit()) or "2"
     ours = ("gemm_", "quant_act", "pack_", "unpack_", "transpose_", "splitk_")
-    lines = [f"# rocprofv3 kernel statistics, {tag}", f"# command: {CMD_KT}",
+    lines = [f"# rocprofv3 kernel statistics, {tag}", f"# command: {CMD_KT.format(cfg=cfg)}",
              f"# {'kernel':68s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}"]
     with open(os.path.join(in_dir, "kt_kernel_stats.csv")) as f:
         for r in csv.DictReader(f):
@@ -59,8 +61,8 @@ def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
     f_scale = CAL_BYTES / 1024.0 / fetch[cal][1]
     w_scale = CAL_BYTES / 1024.0 / write[cal][1]
     lines = [f"# HBM traffic per dispatch from rocprofv3 counters, {tag}",
-             f"# commands: {CMD_PMC.format(c='FETCH_SIZE', o='fetch')}",
-             f"#           {CMD_PMC.format(c='WRITE_SIZE', o='write')}",
+             f"# commands: {CMD_PMC.format(c='FETCH_SIZE', o='fetch', cfg=cfg)}",
+             f"#           {CMD_PMC.format(c='WRITE_SIZE', o='write', cfg=cfg)}",
              f"# calibration: one 256 MiB device copy reads FETCH_SIZE = {fetch[cal][1]:.1f} KiB, "
              f"WRITE_SIZE = {write[cal][1]:.1f} KiB",
              f"#   -> scale factors {f_scale:.3f} (fetch), {w_scale:.3f} (write)",
@@ -75,9 +77,23 @@ def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
         lines.append(f"  {k:68s} {fetch[k][0]:6d} {fb/1e6:10.2f} {wb/1e6:10.2f} {(fb+wb)/1e6:10.2f}")
     with open(os.path.join(out_dir, f"{tag}_hbm_counters.txt"), "w") as f:
         f.write("\n".join(lines) + "\n")
-    with open(os.path.join(out_dir, "hbm_traffic.json"), "w") as f:
-        json.dump({"source": f"{tag}_hbm_counters.txt", "fetch_scale": round(f_scale, 4),
-                   "write_scale": round(w_scale, 4), "bytes_per_launch": per_launch}, f, indent=1)
+    # one table for bench.py, merged over the workloads summarised so far (kernel
+    # symbols differ between workloads; a repeated symbol takes the newest figure)
+    path = os.path.join(out_dir, "hbm_traffic.json")
+    merged, sources = {}, []
+    try:
+        with open(path) as f:
+            old = json.load(f)
+        merged, sources = old.get("bytes_per_launch", {}), old.get("sources", [])
+    except (OSError, ValueError):
+        pass
+    merged.update(per_launch)
+    src = f"{tag}_hbm_counters.txt"
+    if src not in sources:
+        sources.append(src)
+    with open(path, "w") as f:
+        json.dump({"sources": sources, "fetch_scale": round(f_scale, 4),
+                   "write_scale": round(w_scale, 4), "bytes_per_launch": merged}, f, indent=1)
         f.write("\n")
 
 
