@@ -229,8 +229,22 @@ def main() -> int:
             k["seconds"] += t
             k["bytes"] += ab(M, lin.N, lin.K) * L
             k["flops"] += 2 * M * lin.N * lin.K * L
-    dom = max(kernels, key=lambda k: kernels[k]["seconds"])
-    kd = kernels[dom]
+    # The roofline object is for the dominant KERNEL, i.e. one __global__ template in
+    # one mode; its instances (tiles per workgroup and the like, chosen per layer
+    # shape) are separate symbols to the profiler and are added up here.  The
+    # profile summaries carry the same family rows.
+    def family(sym):
+        if sym.startswith("gemm_stream_kernel<"):
+            return "gemm_stream_kernel<" + ",".join(sym.split("<")[1].split(",")[:2]) + ", *>"
+        return sym.split("<")[0] + ("<*>" if "<" in sym else "")
+    families = {}
+    for sym, v in kernels.items():
+        f = families.setdefault(family(sym), dict(launches=0, seconds=0.0, bytes=0, flops=0, mode=v["mode"], symbols=[]))
+        for key in ("launches", "seconds", "bytes", "flops"):
+            f[key] += v[key]
+        f["symbols"].append(sym)
+    dom = max(families, key=lambda k: families[k]["seconds"])
+    kd = families[dom]
     # which roof bounds that kernel: the one its algorithmic work takes longer to reach
     t_hbm = kd["bytes"] / (HBM_PEAK_GBS * 1e9)
     t_mfma = kd["flops"] / (MFMA_PEAK_TFLOPS.get(kd["mode"], 1.0) * 1e12) if kd["flops"] else 0.0
@@ -238,18 +252,20 @@ def main() -> int:
     traffic = None
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
-            traffic = json.load(f).get("bytes_per_launch", {}).get(dom)
+            per = json.load(f).get("bytes_per_launch", {})
+        if all(sym in per for sym in kd["symbols"]):       # launch-weighted mean over the family's symbols
+            traffic = int(sum(per[sym] * kernels[sym]["launches"] for sym in kd["symbols"]) / kd["launches"])
     except (OSError, ValueError):
         pass
     if t_mfma > t_hbm:
         peak = MFMA_PEAK_TFLOPS[kd["mode"]]
         achieved = kd["flops"] / kd["seconds"] / 1e12
-        roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 1), peak=peak,
+        roofline = dict(bound="mfma", kernel=dom, symbols=kd["symbols"], achieved=round(achieved, 1), peak=peak,
                         unit="TFLOP/s" if kd["mode"] == "w4a16" else "TOP/s")
     else:
         peak = HBM_PEAK_GBS
         achieved = kd["bytes"] / kd["seconds"] / 1e9
-        roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=peak, unit="GB/s")
+        roofline = dict(bound="hbm", kernel=dom, symbols=kd["symbols"], achieved=round(achieved, 1), peak=peak, unit="GB/s")
     roofline.update(frac=round(achieved / peak, 4), traffic=traffic,
                     avg_launch_us=round(kd["seconds"] / kd["launches"] * 1e6, 3),
                     alg_bytes_per_launch=kd["bytes"] // kd["launches"],

@@ -224,12 +224,17 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       const int blocks128 = ((N + 127) / 128) * ((M + 127) / 128);
       shape = (M > 64 && blocks128 >= 2 * kNumCU) ? 0 : 2;
     }
-    // K-slices until there are about 1.5 workgroups per compute unit, keeping at least
-    // eight groups per slice (the reduction costs one pass over S fp32 blocks)
+    // K-slices (measured: the exchange costs 4-8 us, so they pay only when the launch
+    // leaves most compute units idle, or when K is very long): double S while fewer
+    // than 192 workgroups and at least 8 groups per slice remain, or while fewer than
+    // 512 workgroups and at least 32 groups per slice remain.
     const TileShape& t0 = shape_of(w4a4, shape);
     const int blocks = ((N + 32 * t0.TN * t0.WGN - 1) / (32 * t0.TN * t0.WGN)) * ((M + 32 * t0.TMW * t0.WGM - 1) / (32 * t0.TMW * t0.WGM));
     S = 1;
-    while (S < 8 && blocks * S < 384 && G / (2 * S) >= 8) S *= 2;
+    while (S < 8) {
+      const int per = G / (2 * S);                     // groups per slice after doubling
+      if ((blocks * S < 192 && per >= 8) || (blocks * S < 512 && per >= 32)) S *= 2; else break;
+    }
   }
   const TileShape& t = shape_of(w4a4, shape);
   const int edge = 32;                  // MFMA tile edge

@@ -32,6 +32,12 @@ def _short(name: str) -> str:
     return name.split("(")[0][:70]
 
 
+def _family(name: str) -> str:
+    if name.startswith("gemm_stream_kernel<"):
+        return "gemm_stream_kernel<" + ",".join(name.split("<")[1].split(",")[:2]) + ", *>"
+    return name.split("<")[0] + ("<*>" if "<" in name else "")
+
+
 def _counter_means(path):
     agg = collections.defaultdict(list)
     with open(path) as f:
@@ -46,12 +52,20 @@ def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
     ours = ("gemm_", "quant_act", "pack_", "unpack_", "transpose_", "splitk_")
     lines = [f"# rocprofv3 kernel statistics, {tag}", f"# command: {CMD_KT.format(cfg=cfg)}",
              f"# {'kernel':68s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}"]
+    fam = collections.OrderedDict()
     with open(os.path.join(in_dir, "kt_kernel_stats.csv")) as f:
         for r in csv.DictReader(f):
             n = _short(r["Name"])
             if n.startswith(ours):
                 lines.append(f"  {n:68s} {int(r['Calls']):6d} {float(r['AverageNs'])/1e3:9.2f} "
                              f"{float(r['MinNs'])/1e3:9.2f} {float(r['MaxNs'])/1e3:9.2f} {float(r['Percentage']):6.2f}")
+                if n.startswith("gemm_"):
+                    e = fam.setdefault(_family(n), [0, 0.0, 0.0])
+                    e[0] += int(r["Calls"]); e[1] += float(r["TotalDurationNs"]); e[2] += float(r["Percentage"])
+    lines.append("# the same, summed over the instances of one kernel template and mode (the unit bench.py's")
+    lines.append("# roofline object is about)")
+    for n, (calls, tot, pct) in fam.items():
+        lines.append(f"  {n:68s} {calls:6d} {tot/calls/1e3:9.2f} {'':9s} {'':9s} {pct:6.2f}")
     with open(os.path.join(out_dir, f"{tag}_kernel_stats.txt"), "w") as f:
         f.write("\n".join(lines) + "\n")
 
