@@ -35,7 +35,8 @@ def rel_err(y, ref):
 
 
 SMALL_SHAPES = [(1, 128, 128), (3, 256, 256), (4, 1152, 1024), (5, 128, 1024), (16, 256, 128),
-                (17, 1152, 256), (33, 144, 384), (70, 272, 640), (130, 48, 1280), (200, 80, 256)]
+                (17, 1152, 256), (33, 144, 384), (70, 272, 640), (130, 48, 1280), (200, 80, 256),
+                (40, 64, 128), (100, 32, 256), (65, 16, 128)]
 
 
 # ------------------------------------------------------------------ pack
@@ -375,6 +376,27 @@ def test_calls_on_a_side_stream(env):
         y = B.gemm_w4a16(blob, dev(torch, x), N)
     s.synchronize()
     assert rel_err(y.cpu().numpy(), orc.gemm_w4a16(x, codes, scales)) <= TOL
+
+
+def test_missing_workspace_is_refused(env, monkeypatch):
+    """A plan with K-slices needs the workspace: none, or a short one, is an error
+    and nothing is launched."""
+    torch, B = env
+    M, N, K = 100, 64, 1024
+    monkeypatch.setenv("QSPEC_TILE_W4A16", "2,2")
+    codes, scales, x = synth.generic_case(80, M, N, K)
+    blob = B.pack_weights(dev(torch, codes), dev(torch, scales))
+    xd = dev(torch, x)
+    need = B.workspace_bytes(M, N, K)
+    assert need > 16384
+    y = torch.full((M, N), 7.0, dtype=torch.float16, device="cuda")
+    L = B.lib()
+    assert L.qspec_gemm_w4a16(blob.data_ptr(), xd.data_ptr(), M, N, K, 128, y.data_ptr(), None, 0, None) == B.ERR_WORKSPACE
+    short = torch.zeros(need - 16, dtype=torch.uint8, device="cuda")
+    assert L.qspec_gemm_w4a16(blob.data_ptr(), xd.data_ptr(), M, N, K, 128, y.data_ptr(), short.data_ptr(),
+                              short.numel(), None) == B.ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert bool((y == 7.0).all())
 
 
 def test_bad_arguments_are_refused_on_device(env):
