@@ -43,10 +43,17 @@ struct StreamRsrc {
   rsrc_t codes, scales, act, sa;
 };
 
+// From this many tiles per workgroup on, the scales of two groups come in one load
+// (below that the two ds_bpermute per tile cost more than the load they replace).
+#ifndef QSPEC_PAIR_SCALES_MIN_NT
+#define QSPEC_PAIR_SCALES_MIN_NT 2
+#endif
+__device__ __host__ inline constexpr bool pair_scales(int nt) { return nt >= QSPEC_PAIR_SCALES_MIN_NT; }
+
 template <bool W4A4, int TM, int NT>
 struct GroupRegs {
   uint4 w[NT];                      // one weight tile slice per n-tile
-  uint2 sw[NT];                     // 4 fp16 weight scales (rows 4*kb .. 4*kb+3 of the tile)
+  uint2 sw[NT];                     // 4 fp16 weight scales (rows 4*kb .. 4*kb+3 of the tile); unused with pair scales
   uint4 a[W4A4 ? TM : TM * 4];      // activation operand(s) of this group
   float sa[W4A4 ? TM : 1];          // activation scales (W4A4)
 };
@@ -83,15 +90,43 @@ __device__ inline void load_group(GroupRegs<W4A4, TM, NT>& R, const StreamRsrc& 
     const bool ok = valid && j < nt_valid;
     const uint32_t T = (uint32_t)(T0 + j);
     R.w[j] = buf_load16_stream(rs.codes, ok ? (T * p.G + g) * 1024u + lane * 16u : kOutOfRange);
-    R.sw[j] = buf_load8(rs.scales, ok ? ((uint32_t)g * p.N + T * 16u + 4u * kb) * 2u : kOutOfRange);
+    if (!pair_scales(NT)) R.sw[j] = buf_load8(rs.scales, ok ? ((uint32_t)g * p.N + T * 16u + 4u * kb) * 2u : kOutOfRange);
   }
+}
+
+// Weight scales of a PAIR of groups (ga: the even step, gb: the odd one) and all NT
+// tiles in one load instruction: lane (c = lane % 16, kb = lane / 16) fetches the four
+// fp16 scales of rows 4*kb .. 4*kb+3 of tile c % NT of group ga (c < NT) or gb
+// (NT <= c < 2*NT).  compute_group fetches them from that lane with ds_bpermute (no
+// LDS memory involved).  Measured: every further load instruction per group costs
+// streaming time even when it hits in cache (the vector memory queue, not DRAM, is
+// what it occupies), so 2*NT small loads per pair became one.
+template <int NT>
+__device__ inline uint2 load_pair_scales(const StreamRsrc& rs, const StreamArgs& p, int ga, int gb, bool va, bool vb,
+                                         int T0, int nt_valid, int lane) {
+  static_assert(2 * NT <= 16, "one lane row holds both groups of all tiles");
+  const int c = lane & 15, kb = lane >> 4;
+  const int q = c / NT, j = c - q * NT;
+  const bool ok = (q == 0 ? va : (q == 1 && vb)) && j < nt_valid;
+  const uint32_t g = (uint32_t)(q == 0 ? ga : gb);
+  return buf_load8(rs.scales, ok ? (g * (uint32_t)p.N + (uint32_t)(T0 + j) * 16u + 4u * kb) * 2u : kOutOfRange);
+}
+
+// The scales of tile j in step Q (0: even, 1: odd) of the pair, from the lane that loaded them.
+template <int NT, int Q>
+__device__ inline uint2 pair_scales_of(uint2 swp, int j, int lane) {
+  const int idx = ((lane & 48) + Q * NT + j) << 2;
+  uint2 r;
+  r.x = (uint32_t)__builtin_amdgcn_ds_bpermute(idx, (int)swp.x);
+  r.y = (uint32_t)__builtin_amdgcn_ds_bpermute(idx, (int)swp.y);
+  return r;
 }
 
 constexpr int kXPitch = 256 + 16;     // bytes per token row of the transpose buffer (odd number of 16-byte slots)
 
-template <bool W4A4, int TM, int NT>
-__device__ inline void compute_group(const GroupRegs<W4A4, TM, NT>& R, float (&facc)[NT][TM][4], uint8_t* xbuf,
-                                     int lane) {
+template <bool W4A4, int TM, int NT, int Q>
+__device__ inline void compute_group(const GroupRegs<W4A4, TM, NT>& R, uint2 swp, float (&facc)[NT][TM][4],
+                                     uint8_t* xbuf, int lane) {
   if (W4A4) {
     // weight operands and scales of all NT tiles first, then token tile by token tile
     // (one unpacked activation operand live at a time: TM goes up to 8)
@@ -100,11 +135,12 @@ __device__ inline void compute_group(const GroupRegs<W4A4, TM, NT>& R, float (&f
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       a[j] = unpack_i8(R.w[j]);
+      const uint2 sq = pair_scales(NT) ? pair_scales_of<NT, Q>(swp, j, lane) : R.sw[j];
       // both int8 operands carry a factor 16: fold 2^-8 into the weight scale (exact)
-      sw[j][0] = half_bits_to_float((uint16_t)(R.sw[j].x & 0xFFFF)) * 0.00390625f;
-      sw[j][1] = half_bits_to_float((uint16_t)(R.sw[j].x >> 16)) * 0.00390625f;
-      sw[j][2] = half_bits_to_float((uint16_t)(R.sw[j].y & 0xFFFF)) * 0.00390625f;
-      sw[j][3] = half_bits_to_float((uint16_t)(R.sw[j].y >> 16)) * 0.00390625f;
+      sw[j][0] = half_bits_to_float((uint16_t)(sq.x & 0xFFFF)) * 0.00390625f;
+      sw[j][1] = half_bits_to_float((uint16_t)(sq.x >> 16)) * 0.00390625f;
+      sw[j][2] = half_bits_to_float((uint16_t)(sq.y & 0xFFFF)) * 0.00390625f;
+      sw[j][3] = half_bits_to_float((uint16_t)(sq.y >> 16)) * 0.00390625f;
     }
 #pragma unroll
     for (int t = 0; t < TM; ++t) {
@@ -139,11 +175,12 @@ __device__ inline void compute_group(const GroupRegs<W4A4, TM, NT>& R, float (&f
       wa[1] = dequant_word(R.w[j].y);
       wa[2] = dequant_word(R.w[j].z);
       wa[3] = dequant_word(R.w[j].w);
+      const uint2 sq = pair_scales(NT) ? pair_scales_of<NT, Q>(swp, j, lane) : R.sw[j];
       float sw[4];
-      sw[0] = half_bits_to_float((uint16_t)(R.sw[j].x & 0xFFFF));
-      sw[1] = half_bits_to_float((uint16_t)(R.sw[j].x >> 16));
-      sw[2] = half_bits_to_float((uint16_t)(R.sw[j].y & 0xFFFF));
-      sw[3] = half_bits_to_float((uint16_t)(R.sw[j].y >> 16));
+      sw[0] = half_bits_to_float((uint16_t)(sq.x & 0xFFFF));
+      sw[1] = half_bits_to_float((uint16_t)(sq.x >> 16));
+      sw[2] = half_bits_to_float((uint16_t)(sq.y & 0xFFFF));
+      sw[3] = half_bits_to_float((uint16_t)(sq.y >> 16));
 #pragma unroll
       for (int t = 0; t < TM; ++t) {
         v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -204,16 +241,22 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
     // queue up.)  The scheduling barriers pin the order "issue loads, then
     // compute": without them the compiler sinks the loads below the arithmetic.
     GroupRegs<W4A4, TM, NT> A, B;
+    uint2 sw_cur = {0u, 0u}, sw_nxt = {0u, 0u};
+    if (pair_scales(NT)) sw_cur = load_pair_scales<NT>(rs, p, grp(0), grp(1), true, 1 < n_g, T0, nt_valid, lane);
     load_group<W4A4, TM, NT>(A, rs, p, grp(0), true, T0, nt_valid, lane);
     for (int it = 0; it < n_g; it += 2) {
+      // the scales of the next pair go out ahead of this pair's second group: they are
+      // back (loads return in order) long before the register move at the bottom
+      if (pair_scales(NT)) sw_nxt = load_pair_scales<NT>(rs, p, grp(it + 2), grp(it + 3), it + 2 < n_g, it + 3 < n_g, T0, nt_valid, lane);
       load_group<W4A4, TM, NT>(B, rs, p, grp(it + 1), it + 1 < n_g, T0, nt_valid, lane);
       __builtin_amdgcn_sched_barrier(0);
-      compute_group<W4A4, TM, NT>(A, facc, xbuf, lane);
+      compute_group<W4A4, TM, NT, 0>(A, sw_cur, facc, xbuf, lane);
       __builtin_amdgcn_sched_barrier(0);
       load_group<W4A4, TM, NT>(A, rs, p, grp(it + 2), it + 2 < n_g, T0, nt_valid, lane);
       __builtin_amdgcn_sched_barrier(0);
-      if (it + 1 < n_g) compute_group<W4A4, TM, NT>(B, facc, xbuf, lane);
+      if (it + 1 < n_g) compute_group<W4A4, TM, NT, 1>(B, sw_cur, facc, xbuf, lane);
       __builtin_amdgcn_sched_barrier(0);
+      sw_cur = sw_nxt;
     }
   }
 
