@@ -272,7 +272,9 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
   };
 #pragma unroll
   for (int base = 0; base < NT * TM; base += kChunk) {
-    __syncthreads();
+    // the buffer must be free: the last pass has been read, and (verify mode) every
+    // wave is done with its transpose buffer, which the sums overwrite
+    if (!W4A4 || base > 0) __syncthreads();
 #pragma unroll
     for (int c = 0; c < kChunk; ++c) {
       const int o = base + c;                      // compile-time: facc stays in registers
