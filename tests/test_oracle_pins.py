@@ -430,3 +430,127 @@ def test_synth_recipe_is_seeded_and_shaped():
     assert len(ch) == 41 and x.dtype == np.float16
     assert np.abs(x[:, ch].astype(np.float32)).mean() > 10
     assert len(synth.outlier_channels(1, 0, 1024)) == 4
+
+
+# ================================================================ acceptance policy and KV overwrite (Sec. 3.1)
+from oracle import accept_oracle as acc   # noqa: E402
+
+
+def _read_kv_fixture(name):
+    out = {}
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        k, v = line.split(":", 1)
+        out[k.strip()] = [int(t) for t in v.split()]
+    return out
+
+
+def _logits_with_top1(top, V, rng, dtype=np.float16):
+    """[rows, V] random logits whose strict maximum in row j sits at top[j]."""
+    lg = rng.standard_normal((len(top), V)).astype(np.float32)
+    for j, t in enumerate(top):
+        lg[j, t] = lg[j].max() + 1.0
+    return lg.astype(dtype)
+
+
+def test_accept_paper_mini_sample():
+    """The worked example the paper gives for gamma = 4 (tests/golden/accept_minisample.txt)."""
+    fx = _read_kv_fixture("accept_minisample.txt")
+    gamma = fx["gamma"][0]
+    rng = np.random.default_rng(5)
+    emitted = 0
+    for c in ("cycle1", "cycle2"):
+        lg = _logits_with_top1(fx[f"{c}_verify_top1"], 128, rng)[None]
+        a, out = acc.greedy_accept(lg, np.array([fx[f"{c}_draft"]], dtype=np.int32))
+        assert a.tolist() == fx[f"{c}_accepted"]
+        assert out[0].tolist() == fx[f"{c}_out"]
+        emitted += int(a[0]) + 1
+    assert gamma == 4 and emitted == fx["tokens_after_two_cycles"][0] == 8   # "commences from the ninth token"
+
+
+def test_accept_equals_longest_common_prefix_formulation():
+    """Independent formulation with library routines: a = length of the longest common
+    prefix of the drafts and the verify pass's greedy tokens (np.argmax returns the first
+    maximum); the emitted token is the greedy token at position a."""
+    rng = np.random.default_rng(11)
+    for V, gamma, B in [(3, 3, 64), (5, 5, 64), (17, 1, 32), (2, 4, 64)]:
+        lg = rng.integers(-3, 4, (B, gamma + 1, V)).astype(np.float16)      # many ties and many matches
+        draft = rng.integers(0, V, (B, gamma)).astype(np.int32)
+        a, out = acc.greedy_accept(lg, draft)
+        greedy = np.argmax(lg.astype(np.float64), axis=2)
+        eq = (greedy[:, :gamma] == draft).astype(np.int64)
+        a_ref = np.cumprod(eq, axis=1).sum(axis=1)
+        assert a.tolist() == a_ref.tolist()
+        for b in range(B):
+            n = int(a[b])
+            assert out[b, :n].tolist() == draft[b, :n].tolist()
+            assert out[b, n] == greedy[b, n]
+            assert (out[b, n + 1:] == -1).all()
+            if n < gamma:
+                assert out[b, n] != draft[b, n]          # a rejected draft is never what gets emitted
+
+
+def test_accept_brute_force_all_small_cases():
+    """Every combination of greedy tokens and drafts for V = 3, gamma = 2."""
+    V, gamma = 3, 2
+    import itertools
+    for greedy in itertools.product(range(V), repeat=gamma + 1):
+        lg = np.full((1, gamma + 1, V), -1.0, dtype=np.float16)
+        for j, t in enumerate(greedy):
+            lg[0, j, t] = 2.0
+        for draft in itertools.product(range(V), repeat=gamma):
+            a, out = acc.greedy_accept(lg, np.array([draft], dtype=np.int32))
+            if draft[0] != greedy[0]:
+                exp_a, exp_out = 0, [greedy[0], -1, -1]
+            elif draft[1] != greedy[1]:
+                exp_a, exp_out = 1, [draft[0], greedy[1], -1]
+            else:
+                exp_a, exp_out = 2, [draft[0], draft[1], greedy[2]]
+            assert int(a[0]) == exp_a and out[0].tolist() == exp_out
+
+
+def test_accept_ties_take_the_lowest_token_id_and_infinities_are_ordered():
+    lg = np.zeros((1, 2, 6), dtype=np.float16)
+    lg[0, 0, [2, 4]] = 3.0                       # tie between 2 and 4 -> 2
+    lg[0, 1, :] = -np.inf
+    lg[0, 1, 5] = -60000.0                       # the only finite value wins over -inf
+    a, out = acc.greedy_accept(lg, np.array([[4]], dtype=np.int32))
+    assert a.tolist() == [0] and out.tolist() == [[2, -1]]
+    a, out = acc.greedy_accept(lg, np.array([[2]], dtype=np.int32))
+    assert a.tolist() == [1] and out.tolist() == [[2, 5]]
+    assert acc.top1(np.array([-np.inf, -np.inf])) == 0
+    assert acc.top1(np.array([1.0, np.inf, np.inf])) == 1
+    assert acc.top1(np.array([-0.0, 0.0])) == 0          # -0 and +0 compare equal: a tie
+
+
+def test_accept_rows_are_independent():
+    rng = np.random.default_rng(3)
+    lg = rng.standard_normal((6, 4, 50)).astype(np.float16)
+    draft = np.argmax(lg[:, :3], axis=2).astype(np.int32)
+    draft[::2, 1] = (draft[::2, 1] + 1) % 50             # reject the second draft of every other sequence
+    a, out = acc.greedy_accept(lg, draft)
+    assert a.tolist() == [1, 3, 1, 3, 1, 3]
+    for b in range(6):
+        a1, out1 = acc.greedy_accept(lg[b:b + 1], draft[b:b + 1])
+        assert a1[0] == a[b] and out1[0].tolist() == out[b].tolist()
+
+
+def test_kv_overwrite_touches_exactly_the_accepted_rows():
+    rng = np.random.default_rng(9)
+    B, S, D, gamma = 4, 12, 8, 3
+    cache = rng.standard_normal((B, S, D)).astype(np.float16)
+    kv = rng.standard_normal((B, gamma + 1, D)).astype(np.float16)
+    a = np.array([0, 3, 1, 2], dtype=np.int32)
+    pos = np.array([5, 0, 10, 11], dtype=np.int32)       # the last one runs off the end of the cache
+    new = acc.kv_overwrite(cache, kv, a, pos)
+    for b in range(B):
+        for s in range(S):
+            j = s - int(pos[b])
+            if 0 <= j <= int(a[b]):
+                assert (new[b, s] == kv[b, j]).all()
+            else:
+                assert (new[b, s] == cache[b, s]).all()
+    assert (cache != new).any()                          # the input itself is not modified ...
+    assert acc.kv_overwrite(new, kv, a, pos).tobytes() == new.tobytes()   # ... and the step is idempotent
