@@ -145,6 +145,48 @@ int qspec_gemm_w4a4_partials(const void* packed, const uint8_t* qa,
                              int n0, int n_count, int32_t* partials, void* stream);
 
 /*
+ * Greedy acceptance after the verify pass (paper Sec. 3.1, "Verify Phase" and
+ * "Acceptance Policy").  The verify pass takes, per sequence, the last committed
+ * token followed by the gamma drafted tokens and returns gamma + 1 rows of
+ * logits; row j is the distribution of the token after input j.  Draft j
+ * (0-based) is accepted exactly when every earlier draft was accepted and it
+ * equals the top-1 token of row j; the first rejection discards the later
+ * drafts.  The token emitted after the accepted ones is the top-1 of the row
+ * where the walk stopped (the corrected token, or one extra token when all
+ * gamma drafts were accepted).  Top-1 under ties: the lowest token id; -0 and
+ * +0 are equal.  NaN logits: behaviour unspecified.
+ *   logits_f16    fp16 [B, gamma+1, V] row-major, 16-byte aligned;
+ *   draft_tokens  int32 [B, gamma];
+ *   n_accept      out, int32 [B], number of accepted drafts (0..gamma);
+ *   out_tokens    out, int32 [B, gamma+1]: the accepted drafts, then the emitted
+ *                 token, then -1;
+ *   workspace     at least qspec_accept_workspace_bytes(B, gamma, V) bytes of
+ *                 scratch, 16-byte aligned, contents meaningless before and after
+ *                 (nothing to clear, no counters).
+ * int32 arrays need 4-byte alignment only.  B >= 1, gamma >= 1, V >= 1,
+ * B*(gamma+1) <= 65535; otherwise QSPEC_ERR_SHAPE.
+ */
+size_t qspec_accept_workspace_bytes(int B, int gamma, int V);
+int qspec_greedy_accept(const void* logits_f16, const int32_t* draft_tokens, int B, int gamma, int V,
+                        int32_t* n_accept, int32_t* out_tokens,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * KV-cache overwrite (paper Sec. 3.1, "KV Cache Overwriting"): the cache entries
+ * of the accepted tokens are replaced by the ones the verify pass computed.
+ * For every sequence b, rows 0 .. n_accept[b] of kv_verify (row 0 belongs to the
+ * last committed token, row j >= 1 to draft j-1) are copied to cache rows
+ * pos[b] .. pos[b] + n_accept[b]; rows after the first rejection are not
+ * copied, target rows outside [0, S) are skipped, n_accept is clamped to
+ * [0, gamma].  Call it once for K and once for V (or once for a fused layout).
+ *   kv_verify_f16 fp16 [B, gamma+1, D];  cache_f16 in/out, fp16 [B, S, D];
+ *   n_accept, pos int32 [B] (device memory; n_accept as written by
+ *   qspec_greedy_accept);  D a positive multiple of 8.
+ */
+int qspec_kv_overwrite(const void* kv_verify_f16, const int32_t* n_accept, const int32_t* pos,
+                       int B, int gamma, int D, int S, void* cache_f16, void* stream);
+
+/*
  * Debug entry: name of the device kernel the GEMM entry points select for an
  * (M,N,K) problem, e.g. "gemm_stream_kernel<false, 2, 3>" (mode 0 = W4A16
  * verify, 1 = W4A4 draft).  It matches the symbol a profiler reports, so that

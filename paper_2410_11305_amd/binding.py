@@ -19,6 +19,7 @@ EXPORTS = (
     "qspec_status_string", "qspec_version", "qspec_packed_weight_bytes", "qspec_workspace_bytes",
     "qspec_pack_weights", "qspec_unpack_weights", "qspec_quant_act", "qspec_gemm_w4a4",
     "qspec_gemm_w4a16", "qspec_gemm_w4a4_partials", "qspec_describe_kernel",
+    "qspec_accept_workspace_bytes", "qspec_greedy_accept", "qspec_kv_overwrite",
 )
 
 
@@ -64,6 +65,12 @@ def lib() -> ctypes.CDLL:
     L.qspec_gemm_w4a4_partials.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, vp, vp]
     L.qspec_describe_kernel.restype = ci
     L.qspec_describe_kernel.argtypes = [ci, ci, ci, ci, ci, ctypes.c_char_p, sz]
+    L.qspec_accept_workspace_bytes.restype = sz
+    L.qspec_accept_workspace_bytes.argtypes = [ci, ci, ci]
+    L.qspec_greedy_accept.restype = ci
+    L.qspec_greedy_accept.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]
+    L.qspec_kv_overwrite.restype = ci
+    L.qspec_kv_overwrite.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
     _lib = L
     return L
 
@@ -198,3 +205,37 @@ def gemm_w4a4_partials(packed: torch.Tensor, qa: torch.Tensor, N: int, n0: int, 
                                           _dev(partials, torch.int32, "partials"), _stream()),
            "qspec_gemm_w4a4_partials")
     return partials
+
+
+def accept_workspace_bytes(B: int, gamma: int, V: int) -> int:
+    return lib().qspec_accept_workspace_bytes(B, gamma, V)
+
+
+def greedy_accept(logits: torch.Tensor, draft: torch.Tensor, n_accept: torch.Tensor = None,
+                  out_tokens: torch.Tensor = None, workspace: torch.Tensor = None):
+    """logits fp16 [B, gamma+1, V], draft int32 [B, gamma] -> (n_accept int32 [B], out_tokens int32 [B, gamma+1])."""
+    B, rows, V = logits.shape
+    gamma = rows - 1
+    if n_accept is None:
+        n_accept = torch.empty((B,), dtype=torch.int32, device=logits.device)
+    if out_tokens is None:
+        out_tokens = torch.empty((B, rows), dtype=torch.int32, device=logits.device)
+    if workspace is None:
+        workspace = torch.empty(max(accept_workspace_bytes(B, gamma, V), 16), dtype=torch.uint8, device=logits.device)
+    _check(lib().qspec_greedy_accept(_dev(logits, torch.float16, "logits"), _dev(draft, torch.int32, "draft"),
+                                     B, gamma, V, _dev(n_accept, torch.int32, "n_accept"),
+                                     _dev(out_tokens, torch.int32, "out_tokens"),
+                                     _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream()),
+           "qspec_greedy_accept")
+    return n_accept, out_tokens
+
+
+def kv_overwrite(cache: torch.Tensor, kv_verify: torch.Tensor, n_accept: torch.Tensor, pos: torch.Tensor) -> torch.Tensor:
+    """cache fp16 [B, S, D] (updated in place), kv_verify fp16 [B, gamma+1, D], n_accept / pos int32 [B]."""
+    B, S, D = cache.shape
+    gamma = kv_verify.shape[1] - 1
+    _check(lib().qspec_kv_overwrite(_dev(kv_verify, torch.float16, "kv_verify"), _dev(n_accept, torch.int32, "n_accept"),
+                                    _dev(pos, torch.int32, "pos"), B, gamma, D, S,
+                                    _dev(cache, torch.float16, "cache"), _stream()),
+           "qspec_kv_overwrite")
+    return cache

@@ -8,6 +8,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include "accept.hpp"
 #include "common.hpp"
 #include "gemm_generic.hpp"
 #include "gemm_stream.hpp"
@@ -292,6 +293,27 @@ int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s
   }
 }
 
+// ---------------------------------------------------------------- acceptance (after the verify pass)
+// Chunks per logits row: about 4096 logits per workgroup, at most one chunk per lane
+// of the second kernel.  A pure function of V.
+struct ArgmaxPlan { int C, chunk; };
+ArgmaxPlan plan_argmax(int V) {
+  int C = (V + 4095) / 4096;
+  if (C > kArgmaxMaxChunks) C = kArgmaxMaxChunks;
+  if (C < 1) C = 1;
+  int chunk = ((V + C - 1) / C + 7) & ~7;
+  C = (V + chunk - 1) / chunk;
+  return ArgmaxPlan{C, chunk};
+}
+
+inline bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
+
+inline int check_accept_shape(int B, int gamma, int V) {
+  if (B < 1 || gamma < 1 || V < 1) return QSPEC_ERR_SHAPE;
+  if ((long long)B * (gamma + 1) > 65535) return QSPEC_ERR_SHAPE;        // one grid row per logits row
+  return QSPEC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -468,6 +490,45 @@ int qspec_gemm_w4a4_partials(const void* packed, const uint8_t* qa, int M, int N
   dim3 grid(n_count / 16, (M + 15) / 16);
   hipLaunchKernelGGL((gemm_w4a4_generic<1, 4, true>), grid, dim3(256), 0,
                      static_cast<hipStream_t>(stream), a);
+  return launch_status();
+}
+
+size_t qspec_accept_workspace_bytes(int B, int gamma, int V) {
+  if (check_accept_shape(B, gamma, V) != QSPEC_OK) return 0;
+  return (size_t)B * (gamma + 1) * plan_argmax(V).C * sizeof(uint64_t);
+}
+
+int qspec_greedy_accept(const void* logits_f16, const int32_t* draft_tokens, int B, int gamma, int V,
+                        int32_t* n_accept, int32_t* out_tokens,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  if (!logits_f16 || !draft_tokens || !n_accept || !out_tokens || !workspace) return QSPEC_ERR_NULL;
+  if (int st = check_accept_shape(B, gamma, V)) return st;
+  if (misaligned(logits_f16) || misaligned(workspace) || misaligned4(draft_tokens) || misaligned4(n_accept) ||
+      misaligned4(out_tokens))
+    return QSPEC_ERR_ALIGN;
+  if (workspace_bytes < qspec_accept_workspace_bytes(B, gamma, V)) return QSPEC_ERR_WORKSPACE;
+  if (int st = check_device()) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const ArgmaxPlan plan = plan_argmax(V);
+  const int R = B * (gamma + 1);
+  ArgmaxArgs a{static_cast<const uint16_t*>(logits_f16), static_cast<uint64_t*>(workspace), V, plan.C, plan.chunk};
+  if (V % 8 == 0) hipLaunchKernelGGL((argmax_partial_kernel<true>), dim3(plan.C, R), dim3(kArgmaxThreads), 0, s, a);
+  else hipLaunchKernelGGL((argmax_partial_kernel<false>), dim3(plan.C, R), dim3(kArgmaxThreads), 0, s, a);
+  AcceptArgs f{static_cast<const uint64_t*>(workspace), draft_tokens, n_accept, out_tokens, gamma, plan.C};
+  hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(64), 0, s, f);
+  return launch_status();
+}
+
+int qspec_kv_overwrite(const void* kv_verify_f16, const int32_t* n_accept, const int32_t* pos,
+                       int B, int gamma, int D, int S, void* cache_f16, void* stream) {
+  if (!kv_verify_f16 || !n_accept || !pos || !cache_f16) return QSPEC_ERR_NULL;
+  if (B < 1 || gamma < 1 || S < 1 || D < 8 || D % 8 != 0) return QSPEC_ERR_SHAPE;
+  if ((long long)B * (gamma + 1) > 0x7fffffffLL) return QSPEC_ERR_SHAPE;
+  if (misaligned(kv_verify_f16) || misaligned(cache_f16) || misaligned4(n_accept) || misaligned4(pos))
+    return QSPEC_ERR_ALIGN;
+  if (int st = check_device()) return st;
+  KvArgs a{static_cast<const uint4*>(kv_verify_f16), static_cast<uint4*>(cache_f16), n_accept, pos, gamma, D / 8, S};
+  hipLaunchKernelGGL(kv_overwrite_kernel, dim3(B * (gamma + 1)), dim3(256), 0, static_cast<hipStream_t>(stream), a);
   return launch_status();
 }
 

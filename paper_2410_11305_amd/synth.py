@@ -14,6 +14,12 @@ Recipe (NumPy PCG64, seed = 10000*config + 100*layer + stream):
   stream 2  draft x        N(0,1) fp32 [M_draft, K], outlier channels x20, -> fp16
   stream 3  verify x       same, [M_verify, K]
   stream 4  outlier channel indices (without replacement), shared by 2 and 3
+Inputs of the steps after the verify pass (accept_case): stream 5 of a config,
+  logits   N(0, 2) fp32 [B, gamma+1, V] -> fp16, with one planted token per row
+           raised to (row maximum + 4), so the greedy token is known by construction
+  drafts   the planted token of their row with probability p_accept, else another id
+  V is the Llama vocabulary size of the config's model class (32000; 128256 exists
+  in the Llama-3 checkpoints the paper also serves and is covered by the tests).
 """
 from __future__ import annotations
 
@@ -115,3 +121,28 @@ def layer_table(config: int) -> List[dict]:
     return [dict(config=config, layer_index=i, name=l.name, K=l.K, N=l.N,
                  draft_M=cfg.draft_M, verify_M=cfg.verify_M)
             for i, l in enumerate(cfg.layers)]
+
+
+VOCAB = {1: 1024, 2: 32000, 3: 32000, 4: 32000, 5: 32000}     # Llama-2 class vocabulary; config 1 is a toy size
+
+
+def accept_case(seed: int, B: int, gamma: int, V: int, p_accept: float = 0.8):
+    """Logits of a verify pass and drafted tokens: returns (logits fp16 [B, gamma+1, V],
+    draft int32 [B, gamma], planted int32 [B, gamma+1])."""
+    rng = np.random.default_rng(seed)
+    logits = (rng.standard_normal((B, gamma + 1, V), dtype=np.float32) * np.float32(2.0))
+    planted = rng.integers(0, V, size=(B, gamma + 1)).astype(np.int32)
+    top = logits.max(axis=2)
+    for b in range(B):
+        for j in range(gamma + 1):
+            logits[b, j, planted[b, j]] = top[b, j] + np.float32(4.0)
+    draft = planted[:, :gamma].copy()
+    miss = rng.random((B, gamma)) >= p_accept
+    other = rng.integers(1, max(V, 2), size=(B, gamma)).astype(np.int32)
+    draft[miss] = (draft[miss] + other[miss]) % V if V > 1 else draft[miss]
+    return logits.astype(np.float16), draft.astype(np.int32), planted
+
+
+def accept_inputs(config: int):
+    cfg = CONFIGS[config]
+    return accept_case(_seed(config, 0, 5), cfg.batch, cfg.gamma, VOCAB[config])

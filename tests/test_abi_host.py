@@ -69,3 +69,23 @@ def test_other_entries_validate_without_device():
     assert L.qspec_gemm_w4a4_partials(a, a, 1, 32, 128, 128, 16, 32, a, None) == B.ERR_SHAPE
     assert L.qspec_gemm_w4a4_partials(a, a, 1, 32, 128, 128, 0, 0, a, None) == B.ERR_SHAPE
     assert L.qspec_gemm_w4a4_partials(a, a, 1, 32, 128, 128, 0, 32, None, None) == B.ERR_NULL
+
+
+def test_accept_entries_validate_without_device():
+    L = B.lib()
+    a = 4096
+    assert B.accept_workspace_bytes(8, 3, 32000) == 8 * 4 * 8 * 8          # 8 chunks of 4000 logits per row
+    assert B.accept_workspace_bytes(1, 1, 17) == 2 * 8
+    assert B.accept_workspace_bytes(0, 3, 32000) == 0
+    assert B.accept_workspace_bytes(20000, 3, 32000) == 0                  # more than 65535 logits rows
+    assert L.qspec_greedy_accept(None, a, 1, 1, 16, a, a, a, 64, None) == B.ERR_NULL
+    assert L.qspec_greedy_accept(a, a, 1, 1, 16, a, a, None, 0, None) == B.ERR_NULL
+    assert L.qspec_greedy_accept(a, a, 1, 0, 16, a, a, a, 64, None) == B.ERR_SHAPE
+    assert L.qspec_greedy_accept(a, a, 1, 1, 0, a, a, a, 64, None) == B.ERR_SHAPE
+    assert L.qspec_greedy_accept(a + 2, a, 1, 1, 16, a, a, a, 64, None) == B.ERR_ALIGN
+    assert L.qspec_greedy_accept(a, a + 2, 1, 1, 16, a, a, a, 64, None) == B.ERR_ALIGN
+    assert L.qspec_greedy_accept(a, a, 1, 1, 16, a, a, a, 8, None) == B.ERR_WORKSPACE
+    assert L.qspec_kv_overwrite(a, a, a, 1, 1, 12, 4, a, None) == B.ERR_SHAPE    # D not a multiple of 8
+    assert L.qspec_kv_overwrite(a, a, a, 1, 1, 16, 0, a, None) == B.ERR_SHAPE
+    assert L.qspec_kv_overwrite(a, None, a, 1, 1, 16, 4, a, None) == B.ERR_NULL
+    assert L.qspec_kv_overwrite(a, a, a, 1, 1, 16, 4, a + 4, None) == B.ERR_ALIGN
