@@ -271,6 +271,33 @@ def main() -> int:
                     alg_bytes_per_launch=kd["bytes"] // kd["launches"],
                     alg_flops_per_launch=kd["flops"] // kd["launches"])
 
+    # ---- the steps after the verify pass (greedy acceptance, KV-cache overwrite): not part
+    # of the step above, timed on their own at this configuration's batch and draft length
+    lg_h, dr_h, _ = synth.accept_inputs(args.config)
+    Bn, rows, V = lg_h.shape
+    kvD, kvS = lins[0].K, 2048                       # one K (or V) row of a decoder block; cache length 2048
+    lg, dr = to(lg_h), to(dr_h)
+    n_acc = torch.empty((Bn,), dtype=torch.int32, device=dev)
+    out_tok = torch.empty((Bn, rows), dtype=torch.int32, device=dev)
+    ws_acc = torch.empty(max(B.accept_workspace_bytes(Bn, rows - 1, V), 16), dtype=torch.uint8, device=dev)
+    kv_new = torch.randn((Bn, rows, kvD), device=dev, generator=gen).half()
+    kv_cache = torch.zeros((Bn, kvS, kvD), dtype=torch.float16, device=dev)
+    kv_pos = torch.randint(0, kvS - rows, (Bn,), device=dev, generator=gen).to(torch.int32)
+    n_rep_small = 16
+    t_acc = time_runner(make_runner(lambda: [B.greedy_accept(lg, dr, n_acc, out_tok, ws_acc) for _ in range(n_rep_small)]),
+                        reps, 2) / n_rep_small
+    t_kv = time_runner(make_runner(lambda: [B.kv_overwrite(kv_cache, kv_new, n_acc, kv_pos) for _ in range(n_rep_small)]),
+                       reps, 2) / n_rep_small
+    acc_bytes = Bn * rows * V * 2 + Bn * (rows - 1) * 4 + Bn * (rows + 1) * 4
+    kv_bytes = int((n_acc.sum().item() + Bn) * kvD * 2 * 2)
+    after_verify = {
+        "greedy_accept": dict(B=Bn, gamma=rows - 1, V=V, us=round(t_acc * 1e6, 3), launches=2,
+                              GBps=round(acc_bytes / t_acc / 1e9, 1), hbm_frac=round(acc_bytes / t_acc / 1e9 / HBM_PEAK_GBS, 4),
+                              accepted_per_cycle=round(float(n_acc.float().mean().item()), 3)),
+        "kv_overwrite": dict(B=Bn, gamma=rows - 1, D=kvD, S=kvS, us=round(t_kv * 1e6, 3), launches=1,
+                             GBps=round(kv_bytes / t_kv / 1e9, 1)),
+    }
+
     # ---- CPU baseline: the oracle on one decoder block (bounded sample)
     cpu = None
     if not args.no_cpu_baseline:
@@ -330,6 +357,7 @@ def main() -> int:
         "same_shape": {"w4a4_draft_pass_us": round((t_4 + t_q) * 1e6, 1),
                        "w4a16_at_draft_M_pass_us": round(t_16d * 1e6, 1)},
         "pack_weights_GBps": round(pack_bytes / t_pack / 1e9, 1) if t_pack > 0 else None,
+        "after_verify": after_verify,
     }
     print(json.dumps(out))
     return 0
