@@ -212,6 +212,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
   const int T0 = tb * NT;
   const int nt_valid = min(NT, p.N / 16 - T0);        // >= 1 by construction of the grid
   const int G = p.G;
+  // token-row blocks along gridDim.y (only without K-slices): this workgroup owns rows m_base .. m_base + 16*TM - 1
+  const int m_base = (int)blockIdx.y * (16 * TM);
+  const int Mloc = p.M - m_base;
+  if (Mloc <= 0) return;                           // (the whole workgroup: uniform)
+  uint16_t* const yloc = p.y + (size_t)m_base * p.N;
   const int g0 = (int)(((long long)slice * G) / p.S), g1 = (int)(((long long)(slice + 1) * G) / p.S);
   // groups of this wave: g0 + wave, g0 + wave + W, ...  (n_g of them, possibly none)
   const int n_g = max(0, (g1 - g0 - wave + W - 1) / W);
@@ -229,8 +234,9 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
     StreamRsrc rs;
     rs.codes = make_rsrc(p.codes, (uint32_t)((size_t)p.N * p.K / 2));
     rs.scales = make_rsrc(p.scalesT, (uint32_t)((size_t)p.N * G * 2));
-    rs.act = make_rsrc(p.act, (uint32_t)(W4A4 ? (size_t)p.M * p.K / 2 : (size_t)p.M * p.K * 2));
-    rs.sa = make_rsrc(W4A4 ? (const void*)p.sa : p.act, (uint32_t)((size_t)p.M * G * 4));
+    const uint8_t* act0 = static_cast<const uint8_t*>(p.act) + (size_t)m_base * (W4A4 ? p.K / 2 : p.K * 2);
+    rs.act = make_rsrc(act0, (uint32_t)(W4A4 ? (size_t)Mloc * p.K / 2 : (size_t)Mloc * p.K * 2));
+    rs.sa = make_rsrc(W4A4 ? (const void*)(p.sa + (size_t)m_base * G) : (const void*)act0, (uint32_t)((size_t)Mloc * G * 4));
     // Workgroups start at different points of their K sequence so that the 256
     // CUs do not all ask L2 for the same activation lines at the same moment.
     const int rot = (int)(blockIdx.x % (unsigned)n_g);
@@ -301,11 +307,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
         store_shared_f2(f + 2, s[2], s[3]);
       } else {
         const int m = 16 * t + r16;
-        if (j < nt_valid && m < p.M) {
+        if (j < nt_valid && m < Mloc) {
           uint2 out;
           out.x = (uint32_t)float_to_half_bits(s[0]) | ((uint32_t)float_to_half_bits(s[1]) << 16);
           out.y = (uint32_t)float_to_half_bits(s[2]) | ((uint32_t)float_to_half_bits(s[3]) << 16);
-          *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + (T0 + j) * 16 + 4 * kb) = out;
+          *reinterpret_cast<uint2*>(yloc + (size_t)m * p.N + (T0 + j) * 16 + 4 * kb) = out;
         }
       }
     }
@@ -321,11 +327,11 @@ __global__ __launch_bounds__(kStreamWaves * 64) void gemm_stream_kernel(StreamAr
       s[0] += a.x; s[1] += a.y; s[2] += b.x; s[3] += b.y;
     }
     const int m = 16 * t + r16;
-    if (j < nt_valid && m < p.M) {
+    if (j < nt_valid && m < Mloc) {
       uint2 out;
       out.x = (uint32_t)float_to_half_bits(s[0]) | ((uint32_t)float_to_half_bits(s[1]) << 16);
       out.y = (uint32_t)float_to_half_bits(s[2]) | ((uint32_t)float_to_half_bits(s[3]) << 16);
-      *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + (T0 + j) * 16 + 4 * kb) = out;
+      *reinterpret_cast<uint2*>(yloc + (size_t)m * p.N + (T0 + j) * 16 + 4 * kb) = out;
     }
   }
 }

@@ -86,24 +86,33 @@ constexpr int kStreamMaxM4 = 64;
 constexpr size_t kTicketBytes = 16384;                 // head of the workspace: arrival counters
 constexpr int kMaxTickets = (int)(kTicketBytes / 4);
 
-// Plan of the streaming kernel: NT adjacent n-tiles per workgroup, S K-slices.
-// A pure function of (mode, M, N, K), so that qspec_workspace_bytes and the GEMM
-// entry points agree.  QSPEC_STREAM_W4A4 / QSPEC_STREAM_W4A16 = "NT,S" override the
-// heuristic (benchmark A/B only).
-struct StreamPlan { int nt, S, blocks; };
-inline int stream_tm(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8; }   // 16-token tiles per workgroup
+// Plan of the streaming kernel: NT adjacent n-tiles per workgroup, S K-slices, ms
+// token-row blocks.  A pure function of (mode, M, N, K), so that qspec_workspace_bytes
+// and the GEMM entry points agree.  QSPEC_STREAM_W4A4 / QSPEC_STREAM_W4A16 = "NT,S" or
+// "NT,S,MS" override the heuristic (benchmark A/B only).
+struct StreamPlan {
+  int nt, S, blocks;
+  int ms;       // token-row blocks (gridDim.y); block y owns rows y*16*tm .. (y+1)*16*tm - 1
+  int tm;       // 16-token tiles per workgroup (the kernel's TM)
+};
+inline int stream_tm(int M) { return M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8; }   // 16-token tiles that cover M rows
 constexpr int kStreamNts[] = {1, 2, 3, 4, 6};
+inline bool stream_nt_ok(int nt, int tm) {
+  for (int v : kStreamNts) if (v == nt) return nt * tm <= 16;      // 4 accumulator registers per tile pair; beyond 64 the kernel spills
+  return false;
+}
+// tiles per workgroup when the rows are dealt to ms blocks: ceil(M / ms) rows, in whole tiles
+inline int stream_tm_split(int M, int ms) { return stream_tm(16 * (((M + ms - 1) / ms + 15) / 16)); }
 
 StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
   const int tiles = N / 16, G = K / kGroup;
-  StreamPlan p{1, 1, tiles};
-  int nt = 0, S = 0;
+  int nt = 0, S = 0, ms = 1;
   const char* e = getenv(w4a4 ? "QSPEC_STREAM_W4A4" : "QSPEC_STREAM_W4A16");
-  bool forced = e && sscanf(e, "%d,%d", &nt, &S) == 2 && S >= 1 && S <= G;
-  if (forced) {
-    forced = false;
-    for (int v : kStreamNts) forced = forced || (v == nt && v * stream_tm(M) <= 16);
-  }
+  const int nf = e ? sscanf(e, "%d,%d,%d", &nt, &S, &ms) : 0;
+  bool forced = nf >= 2 && S >= 1 && S <= G;
+  if (nf < 3) ms = 1;
+  if (forced && ms > 1) forced = S == 1 && (ms == 2 || ms == 4);
+  if (forced) forced = stream_nt_ok(nt, stream_tm_split(M, ms));
   if (!forced) {
     // Cost of a plan, in units of one weight tile (1 KB from HBM) per wavefront:
     // rounds over the 256 compute units x groups per wavefront x (NT weight tiles +
@@ -112,12 +121,13 @@ StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
     // exchange (write-through stores, a ticket, S dependent trips to memory) costs
     // 4 to 10 us, more than any of these launches saves; the path stays available
     // to the override and is covered by the tests.
+    ms = 1;
     const int tm = stream_tm(M);
     const double act = w4a4 ? 0.4 * tm : 1.6 * tm;
     double best = 1e30;
     for (int s = 1; s <= 1; s *= 2) {
       for (int v : kStreamNts) {
-        if (v * tm > 16) continue;                        // 4 accumulator registers per tile pair; beyond 64 the kernel spills
+        if (!stream_nt_ok(v, tm)) continue;
         const int blocks = (tiles + v - 1) / v;
         if (s > 1 && blocks > kMaxTickets) continue;
         const int rounds = (blocks * s + kNumCU - 1) / kNumCU;
@@ -126,14 +136,30 @@ StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
         if (cost < best - 1e-9 || (cost < best + 1e-9 && v > nt)) { best = cost; nt = v; S = s; }
       }
     }
+    // Two token-row blocks: with few tiles per workgroup the activation operand, not the
+    // weights, is most of what a compute unit pulls through its L1 (every workgroup
+    // reads ALL of x).  Dealing the rows to two workgroups that own twice the tiles
+    // keeps the number of workgroups, halves that traffic, and lets the partner's
+    // weight reads hit in L2 (both run on the same XCD: their ids differ by a multiple
+    // of 8).  Measured on the 4096- and 5120-wide layers: 16-25 % less time where the
+    // tile count per workgroup is below act/2 (act in weight-tile units: 1.6 per 16
+    // verify-mode tokens, 1.5 per 16 draft-mode tokens for this decision), slower
+    // on the wide layers, where the weights dominate already.
+    if (tm >= 2) {
+      const double act2 = (w4a4 ? 1.5 : 1.6) * tm;
+      const int blocks1 = (tiles + nt - 1) / nt, blocks2 = ((tiles + 2 * nt - 1) / (2 * nt)) * 2;
+      const bool same_rounds = (blocks2 + kNumCU - 1) / kNumCU <= (blocks1 + kNumCU - 1) / kNumCU;
+      if (nt < act2 / 2 && stream_nt_ok(2 * nt, stream_tm_split(M, 2)) && same_rounds) { nt *= 2; ms = 2; }
+    }
   }
-  p.nt = nt; p.S = S; p.blocks = (tiles + nt - 1) / nt;
+  StreamPlan p{};
+  p.nt = nt; p.S = S; p.blocks = (tiles + nt - 1) / nt; p.ms = ms;
+  p.tm = ms > 1 ? stream_tm_split(M, ms) : stream_tm(M);
   return p;
 }
 
-inline size_t stream_ws_bytes(const StreamPlan& p, int M) {
-  const int tm = stream_tm(M);
-  return p.S > 1 ? kTicketBytes + (size_t)p.S * p.blocks * p.nt * tm * 1024 : 0;
+inline size_t stream_ws_bytes(const StreamPlan& p) {
+  return p.S > 1 ? kTicketBytes + (size_t)p.S * p.blocks * p.nt * p.tm * 1024 : 0;
 }
 
 // The draft mode streams up to 64 tokens (its activation operand is a quarter of
@@ -149,7 +175,7 @@ bool use_stream(bool w4a4, int M) {
 
 template <bool W4A4, int TM>
 void launch_stream_tm(const StreamArgs& a, const StreamPlan& plan, hipStream_t s) {
-  dim3 grid(plan.blocks * plan.S), block(kStreamWaves * 64);
+  dim3 grid(plan.blocks * plan.S, plan.ms), block(kStreamWaves * 64);
   switch (plan.nt) {
     case 1: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 1>), grid, block, 0, s, a); break;
     case 2: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 2>), grid, block, 0, s, a); break;
@@ -165,7 +191,7 @@ void launch_stream(StreamArgs a, void* workspace, hipStream_t s) {
   a.S = plan.S;
   a.tickets = static_cast<unsigned*>(workspace);
   a.ws = plan.S > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kTicketBytes) : nullptr;
-  switch (stream_tm(a.M)) {
+  switch (plan.tm) {
     case 1: launch_stream_tm<W4A4, 1>(a, plan, s); break;
     case 2: launch_stream_tm<W4A4, 2>(a, plan, s); break;
     case 4: if constexpr (W4A4) launch_stream_tm<true, 4>(a, plan, s); break;
@@ -343,7 +369,7 @@ size_t qspec_workspace_bytes(int M, int N, int K, int group) {
   // the larger of what the two modes need for this shape
   size_t need[2];
   for (int w4a4 = 0; w4a4 < 2; ++w4a4) {
-    if (use_stream(w4a4 != 0, M)) need[w4a4] = stream_ws_bytes(plan_stream(w4a4 != 0, M, N, K), M);
+    if (use_stream(w4a4 != 0, M)) need[w4a4] = stream_ws_bytes(plan_stream(w4a4 != 0, M, N, K));
     else if (use_generic()) need[w4a4] = 0;
     else need[w4a4] = plan_ws_bytes(w4a4 != 0, plan_tile(w4a4 != 0, M, N, K));
   }
@@ -537,7 +563,8 @@ int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* o
   if (int st = check_shape(M, N, K, group)) return st;
   const char* b = mode_w4a4 ? "true" : "false";
   if (use_stream(mode_w4a4 != 0, M)) {
-    snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, stream_tm(M), plan_stream(mode_w4a4 != 0, M, N, K).nt);
+    const StreamPlan sp = plan_stream(mode_w4a4 != 0, M, N, K);
+    snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, sp.tm, sp.nt);
   } else {
     if (!use_generic()) {
       const TileShape& t = shape_of(mode_w4a4 != 0, plan_tile(mode_w4a4 != 0, M, N, K).shape);

@@ -255,6 +255,36 @@ def test_stream_kernels_with_k_slices(env, monkeypatch, M, plan):
     assert int(ws[:16384].count_nonzero()) == 0
 
 
+@pytest.mark.parametrize("plan", [None, "2,1,2", "4,1,2", "6,1,2", "1,1,2", "2,1,4"])
+@pytest.mark.parametrize("M", [17, 29, 32, 33, 47, 64])
+def test_stream_kernels_with_token_row_blocks(env, monkeypatch, M, plan):
+    """Token rows dealt to two (or four) workgroups that own the same weight tiles:
+    forced plans with every tile count, and the library's own choice (None) on a
+    narrow layer, where it picks two row blocks.  Ragged M: the last block holds
+    fewer rows than the others, or none at all."""
+    torch, B = env
+    N, K = 400, 1408
+    if plan is not None:
+        monkeypatch.setenv("QSPEC_STREAM_W4A4", plan)
+        monkeypatch.setenv("QSPEC_STREAM_W4A16", plan)
+    codes, scales, x = synth.generic_case(900 + M, M, N, K)
+    blob = B.pack_weights(dev(torch, codes), dev(torch, scales))
+    qa, sa, q_ref, s_ref = _check_quant(torch, B, x)
+    ws = B.alloc_workspace(B.workspace_bytes(M, N, K))
+    guard = 321.0
+    buf4 = torch.full((M * N + 256,), guard, dtype=torch.float16, device="cuda")
+    buf16 = torch.full((M * N + 256,), guard, dtype=torch.float16, device="cuda")
+    y4 = B.gemm_w4a4(blob, qa, sa, N, y=buf4[128:128 + M * N].view(M, N), workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err(y4.cpu().numpy(), orc.gemm_w4a4(q_ref, s_ref, codes, scales)) <= TOL
+    assert (buf4[:128] == guard).all() and (buf4[-128:] == guard).all()
+    if M <= 32:           # the verify mode streams up to 32 tokens
+        y16 = B.gemm_w4a16(blob, dev(torch, x), N, y=buf16[128:128 + M * N].view(M, N), workspace=ws)
+        torch.cuda.synchronize()
+        assert rel_err(y16.cpu().numpy(), orc.gemm_w4a16(x, codes, scales)) <= TOL
+        assert (buf16[:128] == guard).all() and (buf16[-128:] == guard).all()
+
+
 def test_tile_kernel_exact_cases(env, monkeypatch):
     """Exactly representable products through the tiled kernels with K-slices:
     any summation order must give the oracle's bits."""
