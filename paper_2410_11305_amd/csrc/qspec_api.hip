@@ -111,7 +111,7 @@ StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
   const int nf = e ? sscanf(e, "%d,%d,%d", &nt, &S, &ms) : 0;
   bool forced = nf >= 2 && S >= 1 && S <= G;
   if (nf < 3) ms = 1;
-  if (forced && ms > 1) forced = S == 1 && (ms == 2 || ms == 4);
+  if (forced && ms > 1) forced = S == 1 && (ms == 2 || ms == 4 || ms == 8);
   if (forced) forced = stream_nt_ok(nt, stream_tm_split(M, ms));
   if (!forced) {
     // Cost of a plan, in units of one weight tile (1 KB from HBM) per wavefront:
@@ -169,6 +169,8 @@ bool use_stream(bool w4a4, int M) {
   if (w4a4) {
     // measured: beyond 64 tokens the tiled kernel wins
     if (const char* e = getenv("QSPEC_STREAM_MAX_W4A4")) { const int v = atoi(e); if (v >= 32 && v <= 128) max_m = v; }
+  } else {
+    if (const char* e = getenv("QSPEC_STREAM_MAX_W4A16")) { const int v = atoi(e); if (v >= 32 && v <= 256) max_m = v; }
   }
   return M <= max_m;
 }

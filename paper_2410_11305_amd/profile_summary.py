@@ -43,13 +43,13 @@ def _counter_means(path):
     with open(path) as f:
         for r in csv.DictReader(f):
             agg[_short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
-    return {k: (len(v), sum(v) / len(v)) for k, v in agg.items()}
+    return {k: (len(v), sum(v) / len(v), max(v)) for k, v in agg.items()}
 
 
 def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
     os.makedirs(out_dir, exist_ok=True)
     cfg = "".join(ch for ch in tag if ch.isdigit()) or "2"
-    ours = ("gemm_", "quant_act", "pack_", "unpack_", "transpose_", "splitk_")
+    ours = ("gemm_", "quant_act", "pack_", "unpack_", "transpose_", "argmax_", "accept_", "kv_overwrite")
     lines = [f"# rocprofv3 kernel statistics, {tag}", f"# command: {CMD_KT.format(cfg=cfg)}",
              f"# {'kernel':68s} {'calls':>6s} {'avg_us':>9s} {'min_us':>9s} {'max_us':>9s} {'pct':>6s}"]
     fam = collections.OrderedDict()
@@ -72,13 +72,15 @@ def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
     fetch = _counter_means(os.path.join(in_dir, "fetch_counter_collection.csv"))
     write = _counter_means(os.path.join(in_dir, "write_counter_collection.csv"))
     cal = "__amd_rocclr_copyBuffer"
-    f_scale = CAL_BYTES / 1024.0 / fetch[cal][1]
-    w_scale = CAL_BYTES / 1024.0 / write[cal][1]
+    # the largest reading among the runtime's copy dispatches is the 256 MiB copy (torch
+    # issues the same copy kernel for a few tiny tensors as well)
+    f_scale = CAL_BYTES / 1024.0 / fetch[cal][2]
+    w_scale = CAL_BYTES / 1024.0 / write[cal][2]
     lines = [f"# HBM traffic per dispatch from rocprofv3 counters, {tag}",
              f"# commands: {CMD_PMC.format(c='FETCH_SIZE', o='fetch', cfg=cfg)}",
              f"#           {CMD_PMC.format(c='WRITE_SIZE', o='write', cfg=cfg)}",
-             f"# calibration: one 256 MiB device copy reads FETCH_SIZE = {fetch[cal][1]:.1f} KiB, "
-             f"WRITE_SIZE = {write[cal][1]:.1f} KiB",
+             f"# calibration: one 256 MiB device copy reads FETCH_SIZE = {fetch[cal][2]:.1f} KiB, "
+             f"WRITE_SIZE = {write[cal][2]:.1f} KiB",
              f"#   -> scale factors {f_scale:.3f} (fetch), {w_scale:.3f} (write)",
              f"# {'kernel':68s} {'n':>6s} {'fetch_MB':>10s} {'write_MB':>10s} {'total_MB':>10s}"]
     per_launch = {}
@@ -86,7 +88,7 @@ def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
         if not k.startswith(ours):
             continue
         fb = fetch[k][1] * f_scale * 1024
-        wb = write.get(k, (0, 0.0))[1] * w_scale * 1024
+        wb = write.get(k, (0, 0.0, 0.0))[1] * w_scale * 1024
         per_launch[k] = int(fb + wb)
         lines.append(f"  {k:68s} {fetch[k][0]:6d} {fb/1e6:10.2f} {wb/1e6:10.2f} {(fb+wb)/1e6:10.2f}")
     with open(os.path.join(out_dir, f"{tag}_hbm_counters.txt"), "w") as f:
