@@ -104,16 +104,58 @@ inline bool stream_nt_ok(int nt, int tm) {
 // tiles per workgroup when the rows are dealt to ms blocks: ceil(M / ms) rows, in whole tiles
 inline int stream_tm_split(int M, int ms) { return stream_tm(16 * (((M + ms - 1) / ms + 15) / 16)); }
 
+// Largest M the streaming kernels take without token-row blocks: 32 verify-mode tokens, 64
+// draft-mode tokens (a draft-mode activation operand is a quarter of a verify-mode one).
+// QSPEC_STREAM_MAX_W4A4 / QSPEC_STREAM_MAX_W4A16 override the bound (benchmark A/B only).
+int stream_base_max(bool w4a4) {
+  int max_m = w4a4 ? kStreamMaxM4 : kStreamMaxM;
+  if (const char* e = getenv(w4a4 ? "QSPEC_STREAM_MAX_W4A4" : "QSPEC_STREAM_MAX_W4A16")) {
+    const int v = atoi(e);
+    if (v >= 32 && v <= (w4a4 ? 128 : 256)) max_m = v;
+  }
+  return max_m;
+}
+
+// Up to 128 tokens on layers no larger than 8192 x 8192 the streaming kernel with token-row
+// blocks beats the tiled kernels when ONE round of workgroups covers the problem (the
+// tiled kernels have too few output blocks to fill the chip there and fall back on
+// K-slices): measured 4096 x 4096 at 128 tokens 16.0 -> 9.7 us (draft) and 15.5 -> 12.4 us
+// (verify), 8192 x 8192 at 128 draft tokens 31.5 -> 27.1 us; with longer K or more than
+// one round the tiled kernels win.  Picks tiles per workgroup, 16-token tiles per row
+// block and the number of row blocks by the cost model of plan_stream; false: no such plan.
+bool plan_wide_stream(bool w4a4, int M, int N, int K, int* nt_out, int* tm_out, int* ms_out) {
+  if (M > 128 || N > 8192 || K > 8192) return false;
+  const int tiles = N / 16;
+  const double c = w4a4 ? 1.5 : 1.6;
+  double best = 1e30;
+  bool found = false;
+  for (int tm = 1; tm <= (w4a4 ? 8 : 2); tm *= 2) {
+    const int ms = (M + 16 * tm - 1) / (16 * tm);
+    if (ms < 2 || ms > 8) continue;
+    for (int v : kStreamNts) {
+      if (!stream_nt_ok(v, tm)) continue;
+      if (((tiles + v - 1) / v) * ms > kNumCU) continue;
+      const double cost = v + c * tm;
+      if (cost < best - 1e-9 || (cost < best + 1e-9 && v > *nt_out)) { best = cost; *nt_out = v; *tm_out = tm; *ms_out = ms; found = true; }
+    }
+  }
+  return found;
+}
+
 StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
   const int tiles = N / 16, G = K / kGroup;
-  int nt = 0, S = 0, ms = 1;
+  int nt = 0, S = 0, ms = 1, tm_wide = 0;
   const char* e = getenv(w4a4 ? "QSPEC_STREAM_W4A4" : "QSPEC_STREAM_W4A16");
   const int nf = e ? sscanf(e, "%d,%d,%d", &nt, &S, &ms) : 0;
   bool forced = nf >= 2 && S >= 1 && S <= G;
   if (nf < 3) ms = 1;
   if (forced && ms > 1) forced = S == 1 && (ms == 2 || ms == 4 || ms == 8);
-  if (forced) forced = stream_nt_ok(nt, stream_tm_split(M, ms));
-  if (!forced) {
+  if (forced) forced = stream_nt_ok(nt, stream_tm_split(M, ms)) && (w4a4 || stream_tm_split(M, ms) <= 2);
+  if (!forced && M > stream_base_max(w4a4)) {
+    StreamPlan none{};                                   // nt == 0: no streaming plan, the tiled kernels take it
+    if (!plan_wide_stream(w4a4, M, N, K, &nt, &tm_wide, &ms)) return none;
+    S = 1;
+  } else if (!forced) {
     // Cost of a plan, in units of one weight tile (1 KB from HBM) per wavefront:
     // rounds over the 256 compute units x groups per wavefront x (NT weight tiles +
     // the activation operand of the group, which comes from L2 and is re-used for
@@ -154,7 +196,7 @@ StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
   }
   StreamPlan p{};
   p.nt = nt; p.S = S; p.blocks = (tiles + nt - 1) / nt; p.ms = ms;
-  p.tm = ms > 1 ? stream_tm_split(M, ms) : stream_tm(M);
+  p.tm = tm_wide ? tm_wide : (ms > 1 ? stream_tm_split(M, ms) : stream_tm(M));
   return p;
 }
 
@@ -162,17 +204,13 @@ inline size_t stream_ws_bytes(const StreamPlan& p) {
   return p.S > 1 ? kTicketBytes + (size_t)p.S * p.blocks * p.nt * p.tm * 1024 : 0;
 }
 
-// The draft mode streams up to 64 tokens (its activation operand is a quarter of
-// the verify mode's); QSPEC_STREAM_MAX_W4A4 overrides that bound (benchmark A/B only).
-bool use_stream(bool w4a4, int M) {
-  int max_m = w4a4 ? kStreamMaxM4 : kStreamMaxM;
-  if (w4a4) {
-    // measured: beyond 64 tokens the tiled kernel wins
-    if (const char* e = getenv("QSPEC_STREAM_MAX_W4A4")) { const int v = atoi(e); if (v >= 32 && v <= 128) max_m = v; }
-  } else {
-    if (const char* e = getenv("QSPEC_STREAM_MAX_W4A16")) { const int v = atoi(e); if (v >= 32 && v <= 256) max_m = v; }
-  }
-  return M <= max_m;
+bool tile_override(bool w4a4, int* shape, int* S);
+
+bool use_stream(bool w4a4, int M, int N, int K) {
+  if (M <= stream_base_max(w4a4)) return true;
+  int shape, S;
+  if (tile_override(w4a4, &shape, &S)) return false;      // a forced tile shape means the tiled kernel
+  return plan_stream(w4a4, M, N, K).nt > 0;
 }
 
 template <bool W4A4, int TM>
@@ -371,7 +409,7 @@ size_t qspec_workspace_bytes(int M, int N, int K, int group) {
   // the larger of what the two modes need for this shape
   size_t need[2];
   for (int w4a4 = 0; w4a4 < 2; ++w4a4) {
-    if (use_stream(w4a4 != 0, M)) need[w4a4] = stream_ws_bytes(plan_stream(w4a4 != 0, M, N, K));
+    if (use_stream(w4a4 != 0, M, N, K)) need[w4a4] = stream_ws_bytes(plan_stream(w4a4 != 0, M, N, K));
     else if (use_generic()) need[w4a4] = 0;
     else need[w4a4] = plan_ws_bytes(w4a4 != 0, plan_tile(w4a4 != 0, M, N, K));
   }
@@ -440,7 +478,7 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int 
   a.y = static_cast<uint16_t*>(y_f16);
   a.M = M; a.N = N; a.K = K; a.G = K / kGroup;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (use_stream(true, M)) {
+  if (use_stream(true, M, N, K)) {
     StreamArgs st{};
     st.codes = a.codes; st.scalesT = a.scalesT; st.act = qa; st.sa = sa; st.y = a.y;
     st.M = M; st.N = N; st.K = K; st.G = a.G;
@@ -478,7 +516,7 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16, int M, int N, int K,
   a.y = static_cast<uint16_t*>(y_f16);
   a.M = M; a.N = N; a.K = K; a.G = K / kGroup;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (use_stream(false, M)) {
+  if (use_stream(false, M, N, K)) {
     StreamArgs st{};
     st.codes = a.codes; st.scalesT = a.scalesT; st.act = x_f16; st.y = a.y;
     st.M = M; st.N = N; st.K = K; st.G = a.G;
@@ -564,7 +602,7 @@ int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* o
   if (!out || cap == 0) return QSPEC_ERR_NULL;
   if (int st = check_shape(M, N, K, group)) return st;
   const char* b = mode_w4a4 ? "true" : "false";
-  if (use_stream(mode_w4a4 != 0, M)) {
+  if (use_stream(mode_w4a4 != 0, M, N, K)) {
     const StreamPlan sp = plan_stream(mode_w4a4 != 0, M, N, K);
     snprintf(out, cap, "gemm_stream_kernel<%s, %d, %d>", b, sp.tm, sp.nt);
   } else {

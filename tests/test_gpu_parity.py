@@ -256,12 +256,13 @@ def test_stream_kernels_with_k_slices(env, monkeypatch, M, plan):
 
 
 @pytest.mark.parametrize("plan", [None, "2,1,2", "4,1,2", "6,1,2", "1,1,2", "2,1,4"])
-@pytest.mark.parametrize("M", [17, 29, 32, 33, 47, 64])
+@pytest.mark.parametrize("M", [17, 29, 32, 33, 47, 64, 65, 100, 128])
 def test_stream_kernels_with_token_row_blocks(env, monkeypatch, M, plan):
-    """Token rows dealt to two (or four) workgroups that own the same weight tiles:
+    """Token rows dealt to two or more workgroups that own the same weight tiles:
     forced plans with every tile count, and the library's own choice (None) on a
-    narrow layer, where it picks two row blocks.  Ragged M: the last block holds
-    fewer rows than the others, or none at all."""
+    narrow layer, where it picks row blocks up to 128 tokens.  Ragged M: the last
+    block holds fewer rows than the others, or none at all.  (A forced plan that has
+    no instance for this M falls back to the library's choice.)"""
     torch, B = env
     N, K = 400, 1408
     if plan is not None:
@@ -278,11 +279,13 @@ def test_stream_kernels_with_token_row_blocks(env, monkeypatch, M, plan):
     torch.cuda.synchronize()
     assert rel_err(y4.cpu().numpy(), orc.gemm_w4a4(q_ref, s_ref, codes, scales)) <= TOL
     assert (buf4[:128] == guard).all() and (buf4[-128:] == guard).all()
-    if M <= 32:           # the verify mode streams up to 32 tokens
-        y16 = B.gemm_w4a16(blob, dev(torch, x), N, y=buf16[128:128 + M * N].view(M, N), workspace=ws)
-        torch.cuda.synchronize()
-        assert rel_err(y16.cpu().numpy(), orc.gemm_w4a16(x, codes, scales)) <= TOL
-        assert (buf16[:128] == guard).all() and (buf16[-128:] == guard).all()
+    y16 = B.gemm_w4a16(blob, dev(torch, x), N, y=buf16[128:128 + M * N].view(M, N), workspace=ws)
+    torch.cuda.synchronize()
+    assert rel_err(y16.cpu().numpy(), orc.gemm_w4a16(x, codes, scales)) <= TOL
+    assert (buf16[:128] == guard).all() and (buf16[-128:] == guard).all()
+    if plan is None:      # one round of workgroups covers this small layer: the streaming kernel takes it in both modes
+        assert B.describe_kernel(True, M, N, K).startswith("gemm_stream_kernel")
+        assert B.describe_kernel(False, M, N, K).startswith("gemm_stream_kernel")
 
 
 def test_tile_kernel_exact_cases(env, monkeypatch):
