@@ -289,19 +289,27 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       shape = 1;
     } else {
       const int blocks128 = ((N + 127) / 128) * ((M + 127) / 128);
-      shape = (M > 64 && blocks128 >= 2 * kNumCU) ? 0 : 2;
+      const int blocks64 = ((N + 127) / 128) * ((M + 63) / 64);
+      // 128 x 64 blocks: with at most one workgroup per compute unit the instance with
+      // four activation stages hides more latency (measured 23.5 -> 21.4 us at 128 tokens
+      // on 12288 x 4096); with more workgroups than compute units the three-per-unit instance
+      shape = (M > 64 && blocks128 >= 2 * kNumCU) ? 0 : (blocks64 <= kNumCU ? 3 : 2);
     }
-    // K-slices (measured: the exchange costs 4-8 us, so they pay only when the launch
-    // leaves most compute units idle, or when K is very long): double S while fewer
-    // than 192 workgroups and at least 8 groups per slice remain, or while fewer than
-    // 512 workgroups and at least 32 groups per slice remain.
+    // K-slices (measured: the exchange costs 4-8 us).  They pay while ALL workgroups
+    // still run at once on compute units of their own: S = the largest count (not only
+    // powers of two: slices are cut proportionally) with blocks * S <= 256 and at least 8
+    // groups per slice.  Beyond that the extra workgroups queue behind the first ones
+    // and only the exchange is added (172 blocks of a 22016-wide layer at 64 tokens:
+    // 25.2 us unsliced, 29.6 us in two slices; 128 blocks of 8192 x 8192 at 128 tokens:
+    // 40.9 -> 29.7 us).  With very long K (at least 32 groups per slice after doubling)
+    // doubling still pays while fewer than 512 workgroups result.
     const TileShape& t0 = shape_of(w4a4, shape);
     const int blocks = ((N + 32 * t0.TN * t0.WGN - 1) / (32 * t0.TN * t0.WGN)) * ((M + 32 * t0.TMW * t0.WGM - 1) / (32 * t0.TMW * t0.WGM));
-    S = 1;
-    while (S < 8) {
-      const int per = G / (2 * S);                     // groups per slice after doubling
-      if ((blocks * S < 192 && per >= 8) || (blocks * S < 512 && per >= 32)) S *= 2; else break;
-    }
+    S = kNumCU / blocks;
+    if (S > 8) S = 8;
+    while (S > 1 && G / S < 8) --S;
+    if (S < 1) S = 1;
+    while (S < 8 && blocks * S < 512 && G / (2 * S) >= 32) S *= 2;
   }
   const TileShape& t = shape_of(w4a4, shape);
   const int edge = 32;                  // MFMA tile edge
