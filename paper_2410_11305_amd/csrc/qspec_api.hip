@@ -293,7 +293,10 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       // 128 x 64 blocks: with at most one workgroup per compute unit the instance with
       // four activation stages hides more latency (measured 23.5 -> 21.4 us at 128 tokens
       // on 12288 x 4096); with more workgroups than compute units the three-per-unit instance
-      shape = (M > 64 && blocks128 >= 2 * kNumCU) ? 0 : (blocks64 <= kNumCU ? 3 : 2);
+      // (128 x 128 blocks also when one per compute unit exists and K is long enough for the
+      // two K-slices that make it two: 28672 -> 8192 at 512 tokens 254 -> 236 us)
+      const bool big = M > 64 && (blocks128 >= 2 * kNumCU || (blocks128 >= kNumCU && G >= 128));
+      shape = big ? 0 : (blocks64 <= kNumCU ? 3 : 2);
     }
     // K-slices (measured: the exchange costs 4-8 us).  They pay while ALL workgroups
     // still run at once on compute units of their own: S = the largest count (not only
