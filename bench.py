@@ -271,6 +271,30 @@ def main() -> int:
                     alg_bytes_per_launch=kd["bytes"] // kd["launches"],
                     alg_flops_per_launch=kd["flops"] // kd["launches"])
 
+    # ---- extra rows: both modes at 256 and 512 tokens on this configuration's layers (no
+    # configuration drafts more than 128 tokens; these rows show the draft-mode kernel in
+    # the matrix-bound regime next to the verify-mode kernel at the same shape)
+    extra = {}
+    for Mx in (256, 512):
+        xx = [torch.randn((Mx, lin.K), device=dev, generator=gen).half() for lin in lins]
+        qx = [B.quant_act(t) for t in xx]
+        yx = [torch.empty((Mx, lin.N), dtype=torch.float16, device=dev) for lin in lins]
+        wsx = B.alloc_workspace(max([B.workspace_bytes(Mx, l.N, l.K) for l in lins] + [16]))
+        Lx = min(L, 4)
+        for i, lin in enumerate(lins):
+            for kind in ("w4a4", "w4a16"):
+                def f(i=i, lin=lin, kind=kind):
+                    for l in range(Lx):
+                        if kind == "w4a4":
+                            B.gemm_w4a4(blobs[l][i], qx[i][0], qx[i][1], lin.N, y=yx[i], workspace=wsx)
+                        else:
+                            B.gemm_w4a16(blobs[l][i], xx[i], lin.N, y=yx[i], workspace=wsx)
+                t = time_runner(make_runner(f), 3, 1) / Lx
+                extra[f"{lin.name}.{kind}.M{Mx}"] = dict(
+                    us=round(t * 1e6, 2),
+                    mfma_frac=round(2 * Mx * lin.N * lin.K / t / 1e12 / MFMA_PEAK_TFLOPS[kind], 4))
+        del xx, qx, yx, wsx
+
     # ---- the steps after the verify pass (greedy acceptance, KV-cache overwrite): not part
     # of the step above, timed on their own at this configuration's batch and draft length
     lg_h, dr_h, _ = synth.accept_inputs(args.config)
@@ -358,6 +382,7 @@ def main() -> int:
                        "w4a16_at_draft_M_pass_us": round(t_16d * 1e6, 1)},
         "pack_weights_GBps": round(pack_bytes / t_pack / 1e9, 1) if t_pack > 0 else None,
         "after_verify": after_verify,
+        "extra_rows_M256_M512": extra,
     }
     print(json.dumps(out))
     return 0
