@@ -22,9 +22,9 @@ import sys
 
 CAL_BYTES = 256 << 20
 CMD_KT = ("rocprofv3 --kernel-trace --stats -f csv -d <dir> -o kt -- "
-          "python3 bench.py --config {cfg} --steps 5 --warmup 1 --no-cpu-baseline")
+          "python3 bench.py --config {cfg} --steps 5 --warmup 1 --no-cpu-baseline --no-extra")
 CMD_PMC = ("rocprofv3 --pmc {c} -f csv -d <dir> -o {o} -- "
-           "python3 bench.py --config {cfg} --steps 2 --warmup 1 --no-cpu-baseline --no-graph")
+           "python3 bench.py --config {cfg} --steps 2 --warmup 1 --no-cpu-baseline --no-extra --no-graph")
 
 
 def _short(name: str) -> str:
