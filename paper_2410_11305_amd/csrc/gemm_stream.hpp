@@ -132,6 +132,16 @@ __device__ inline void compute_group(const GroupRegs<W4A4, TM, NT>& R, uint2 swp
     // (one unpacked activation operand live at a time: TM goes up to 8)
     I8Pair a[NT];
     float sw[NT][4];
+    // With two or more token tiles the int32 -> fp32 conversion is folded away: the MFMA
+    // chain starts from the bit pattern of 1.5 * 2^23, so the finished int32 register READ
+    // AS A FLOAT is 12582912 + 256 P exactly (|256 P| <= 2^21: inside the binade, one unit
+    // in the last place = 1), and fma(that, sw, -12582912 * sw) is the correctly rounded
+    // 256 P * sw (the constant is exact: sw has 11 significant bits, 1.5 * 2^23 two).  Two
+    // vector instructions per output and group instead of three, plus one per weight row
+    // and group that the TM token tiles share.
+    constexpr bool kMagic = TM >= 2;
+    constexpr int kMagicBits = 0x4B400000;              // 12582912.0f
+    float swc[NT][4];
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       a[j] = unpack_i8(R.w[j]);
@@ -141,17 +151,29 @@ __device__ inline void compute_group(const GroupRegs<W4A4, TM, NT>& R, uint2 swp
       sw[j][1] = half_bits_to_float((uint16_t)(sq.x >> 16)) * 0.00390625f;
       sw[j][2] = half_bits_to_float((uint16_t)(sq.y & 0xFFFF)) * 0.00390625f;
       sw[j][3] = half_bits_to_float((uint16_t)(sq.y >> 16)) * 0.00390625f;
+      if (kMagic) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) swc[j][r] = sw[j][r] * -12582912.0f;
+      }
     }
 #pragma unroll
     for (int t = 0; t < TM; ++t) {
       const I8Pair b = unpack_i8(R.a[t]);
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        v4i acc = {0, 0, 0, 0};
+        v4i acc = kMagic ? v4i{kMagicBits, kMagicBits, kMagicBits, kMagicBits} : v4i{0, 0, 0, 0};
         acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[j].lo, b.lo, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[j].hi, b.hi, acc, 0, 0, 0);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) facc[j][t][r] += (float)acc[r] * (R.sa[t] * sw[j][r]);
+        for (int r = 0; r < 4; ++r) {
+          if (kMagic) {
+            const int bits = acc[r];                    // (a copy: bit_cast of a vector element lvalue reads element 0)
+            facc[j][t][r] = __builtin_fmaf(__builtin_fmaf(__builtin_bit_cast(float, bits), sw[j][r], swc[j][r]),
+                                           R.sa[t], facc[j][t][r]);
+          } else {
+            facc[j][t][r] += (float)acc[r] * (R.sa[t] * sw[j][r]);
+          }
+        }
       }
     }
   } else {
