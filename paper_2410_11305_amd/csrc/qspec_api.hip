@@ -249,6 +249,9 @@ constexpr TileShape kShapes16[] = {     // verify mode (gemm_tile16w_kernel): TN
     {2, 2, 4, 1, 4, 4, 2},   // 1: 256 x 64, four activation stages
     {1, 2, 4, 1, 4, 2, 3},   // 2: 128 x 64, three workgroups per compute unit
     {1, 2, 4, 1, 4, 4, 2},   // 3: 128 x 64, four activation stages
+    {1, 4, 8, 1, 4, 2, 1},   // 4: 256 x 128, eight wavefronts, one workgroup per compute unit
+    {1, 4, 8, 1, 4, 4, 1},   // 5: 256 x 128, four activation stages
+    {1, 2, 8, 1, 4, 4, 1},   // 6: 256 x 64, eight wavefronts, four activation stages
 };
 constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile4w_kernel): TN, TMW count 32 x 32 tiles; NW = NS = 3
     {1, 4, 4, 1, 3, 3, 2},   // 0: 128 x 128
@@ -258,7 +261,7 @@ constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile4w_kernel): TN, 
     {1, 4, 4, 1, 3, 3, 1},   // 4: 128 x 128, one workgroup per compute unit
 };
 constexpr int kNumTileShapes = 5;
-constexpr int kNumShapes16 = 4;
+constexpr int kNumShapes16 = 7;
 struct TilePlan {
   int shape;      // index into the mode's shape table
   int S;          // K-slices
@@ -297,6 +300,14 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       // two K-slices that make it two: 28672 -> 8192 at 512 tokens 254 -> 236 us)
       const bool big = M > 64 && (blocks128 >= 2 * kNumCU || (blocks128 >= kNumCU && G >= 128));
       shape = big ? 0 : (blocks64 <= kNumCU ? 3 : 2);
+      // 256 x 128 blocks on eight wavefronts (one workgroup per compute unit) halve the
+      // activation bytes a compute unit pulls per output (the global -> LDS transfers of x are
+      // 19 % of the 128 x 128 instance's time), but with one workgroup per unit a ragged
+      // last round costs a whole round: only when the rounds come out (almost) full
+      // (16384 x 8192 at 512 tokens: 134.6 -> 125.0 us; 57344 x 8192: no gain at 87.5 %)
+      const int blocks256 = ((N + 255) / 256) * ((M + 127) / 128);
+      const int rounds256 = (blocks256 + kNumCU - 1) / kNumCU;
+      if (big && M >= 256 && blocks256 * 100 >= rounds256 * kNumCU * 95) shape = 4;
     }
     // K-slices (measured: the exchange costs 4-8 us).  They pay while ALL workgroups
     // still run at once on compute units of their own: S = the largest count (not only
@@ -305,14 +316,15 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
     // and only the exchange is added (172 blocks of a 22016-wide layer at 64 tokens:
     // 25.2 us unsliced, 29.6 us in two slices; 128 blocks of 8192 x 8192 at 128 tokens:
     // 40.9 -> 29.7 us).  With very long K (at least 32 groups per slice after doubling)
-    // doubling still pays while fewer than 512 workgroups result.
+    // doubling still pays while the workgroups stay resident together (two per unit).
     const TileShape& t0 = shape_of(w4a4, shape);
     const int blocks = ((N + 32 * t0.TN * t0.WGN - 1) / (32 * t0.TN * t0.WGN)) * ((M + 32 * t0.TMW * t0.WGM - 1) / (32 * t0.TMW * t0.WGM));
     S = kNumCU / blocks;
     if (S > 8) S = 8;
     while (S > 1 && G / S < 8) --S;
     if (S < 1) S = 1;
-    while (S < 8 && blocks * S < 512 && G / (2 * S) >= 32) S *= 2;
+    const int resident = t0.OCC >= 2 ? 2 * kNumCU : kNumCU;     // workgroups that run at once
+    while (S < 8 && blocks * S < resident && G / (2 * S) >= 32) S *= 2;
   }
   const TileShape& t = shape_of(w4a4, shape);
   const int edge = 32;                  // MFMA tile edge
@@ -366,7 +378,10 @@ int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s
     case 0: return launch_tile16w_inst<1, 4, 4, 1, 4, 2, 2>(a, s);
     case 1: return launch_tile16w_inst<2, 2, 4, 1, 4, 4, 2>(a, s);
     case 2: return launch_tile16w_inst<1, 2, 4, 1, 4, 2, 3>(a, s);
-    default: return launch_tile16w_inst<1, 2, 4, 1, 4, 4, 2>(a, s);
+    case 3: return launch_tile16w_inst<1, 2, 4, 1, 4, 4, 2>(a, s);
+    case 4: return launch_tile16w_inst<1, 4, 8, 1, 4, 2, 1>(a, s);
+    case 5: return launch_tile16w_inst<1, 4, 8, 1, 4, 4, 1>(a, s);
+    default: return launch_tile16w_inst<1, 2, 8, 1, 4, 4, 1>(a, s);
   }
 }
 

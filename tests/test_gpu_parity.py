@@ -195,15 +195,15 @@ def test_all_sixteen_codes_dequantise_exactly(env):
 
 # ------------------------------------------------------------------ tiled kernels (M > 32)
 @pytest.mark.parametrize("S", [1, 3])
-@pytest.mark.parametrize("shape", range(5))
+@pytest.mark.parametrize("shape", range(7))
 def test_tile_kernels_every_workgroup_shape(env, monkeypatch, shape, S):
     """Every instantiated workgroup shape, alone and with 3 K-slices that meet in
     the workspace, on a problem with ragged M, a ragged last n-block and a group
     count (7) that does not divide by the slice count."""
     torch, B = env
     M, N, K = 150, 304, 896
-    monkeypatch.setenv("QSPEC_TILE_W4A4", f"{shape},{S}")
-    monkeypatch.setenv("QSPEC_TILE_W4A16", f"{shape % 4},{S}")     # 5 draft-mode shapes, 4 verify-mode shapes
+    monkeypatch.setenv("QSPEC_TILE_W4A4", f"{shape % 5},{S}")      # 5 draft-mode shapes, 7 verify-mode shapes
+    monkeypatch.setenv("QSPEC_TILE_W4A16", f"{shape},{S}")
     codes, scales, x = synth.generic_case(600 + shape, M, N, K)
     blob = B.pack_weights(dev(torch, codes), dev(torch, scales))
     qa, sa, q_ref, s_ref = _check_quant(torch, B, x)
