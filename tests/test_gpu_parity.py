@@ -36,7 +36,8 @@ def rel_err(y, ref):
 
 SMALL_SHAPES = [(1, 128, 128), (3, 256, 256), (4, 1152, 1024), (5, 128, 1024), (16, 256, 128),
                 (17, 1152, 256), (33, 144, 384), (70, 272, 640), (130, 48, 1280), (200, 80, 256),
-                (40, 64, 128), (100, 32, 256), (65, 16, 128)]
+                (40, 64, 128), (100, 32, 256), (65, 16, 128),
+                (1100, 144, 256), (2050, 272, 384)]          # prefill-sized M: many ragged token blocks
 
 
 # ------------------------------------------------------------------ pack
