@@ -55,6 +55,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="workload configuration (2 = headline)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--vendor-context", action="store_true",
+                    help="also time torch.matmul (the vendor library's plain fp16 GEMM, fp16 weights, no quantisation) "
+                         "on this configuration's verify-mode shapes: a yardstick for what the machine sustains, not a target")
     ap.add_argument("--no-extra", action="store_true",
                     help="skip the rows at 256 and 512 tokens and the verify-mode pass at the draft M (profiling runs: their "
                          "launches would mix into the kernel statistics)")
@@ -300,6 +303,19 @@ def main() -> int:
                     mfma_frac=round(2 * Mx * lin.N * lin.K / t / 1e12 / MFMA_PEAK_TFLOPS[kind], 4))
         del xx, qx, yx, wsx
 
+    # ---- optional yardstick: the vendor library's plain fp16 GEMM on the verify-mode shapes
+    vendor = None
+    if args.vendor_context:
+        vendor = {}
+        for i, lin in enumerate(lins):
+            Rv = max(2, int(1.2e9 // (lin.N * lin.K * 2)) + 1)           # rotate over more fp16 weight bytes than the last-level cache holds
+            Wv = [(torch.randn((lin.N, lin.K), device=dev, generator=gen) * 0.03).half() for _ in range(Rv)]
+            yvv = torch.empty((Mv, lin.N), dtype=torch.float16, device=dev)
+            t = time_runner(make_runner(lambda: [torch.matmul(xv[i], W.t(), out=yvv) for W in Wv]), 3, 1) / Rv
+            vendor[f"{lin.name}.fp16.M{Mv}"] = dict(us=round(t * 1e6, 2), TFLOPs=round(2 * Mv * lin.N * lin.K / t / 1e12, 1),
+                                                     weight_TBps=round(lin.N * lin.K * 2 / t / 1e12, 2))
+            del Wv, yvv
+
     # ---- the steps after the verify pass (greedy acceptance, KV-cache overwrite): not part
     # of the step above, timed on their own at this configuration's batch and draft length
     lg_h, dr_h, _ = synth.accept_inputs(args.config)
@@ -388,6 +404,7 @@ def main() -> int:
         "pack_weights_GBps": round(pack_bytes / t_pack / 1e9, 1) if t_pack > 0 else None,
         "after_verify": after_verify,
         "extra_rows_M256_M512": extra,
+        "vendor_fp16_gemm_context": vendor,
     }
     print(json.dumps(out))
     return 0
