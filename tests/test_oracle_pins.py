@@ -554,3 +554,139 @@ def test_kv_overwrite_touches_exactly_the_accepted_rows():
                 assert (new[b, s] == cache[b, s]).all()
     assert (cache != new).any()                          # the input itself is not modified ...
     assert acc.kv_overwrite(new, kv, a, pos).tobytes() == new.tobytes()   # ... and the step is idempotent
+
+
+# ---------------------------------------------------------------- producers of draft-mode activations
+from oracle import producers_oracle as prod
+
+
+def _f16(values):
+    return np.asarray(values, dtype=np.float16)
+
+
+def _exact_rsqrt_fp32(v: Fraction) -> Fraction:
+    """fp32(1/sqrt(v)) for a positive rational v, by integer square root at 2^-200."""
+    import math
+    scale = 1 << 400
+    root = Fraction(math.isqrt((v.numerator * scale) // v.denominator), 1 << 200)   # sqrt(v), 200 bits
+    return _fl(1 / root, 23, -126)
+
+
+def test_rmsnorm_vs_exact_rationals():
+    rng = np.random.default_rng(41)
+    K = 128
+    x = _f16(rng.standard_normal((3, K)) * 2.0)
+    w = _f16(1.0 + 0.25 * rng.standard_normal(K))
+    eps = np.float32(1e-5)
+    got = prod.rmsnorm_f16(x, w, eps)
+    for m in range(3):
+        ms = sum(Fraction(float(v)) ** 2 for v in x[m]) / K
+        r = _exact_rsqrt_fp32(ms + Fraction(float(eps)))
+        for k in range(K):
+            u = _fl(Fraction(float(x[m, k])) * Fraction(float(w[k])) * r, 23, -126)
+            h = _fl(u, 10, -14)
+            assert Fraction(float(got[m, k])) == h, (m, k)
+
+
+def test_rmsnorm_closed_forms():
+    K = 4096
+    ones = _f16(np.ones(K))
+    # constant row, eps = 0: every output is sign(c) * w
+    for c in (0.37, -3.0, 1024.0):
+        h = prod.rmsnorm_f16(_f16(np.full((1, K), c)), ones, 0.0)
+        assert np.all(h == np.float16(np.sign(c)))
+    w = _f16(np.linspace(0.5, 1.5, K))
+    h = prod.rmsnorm_f16(_f16(np.full((1, K), 2.0)), w, 0.0)
+    assert np.array_equal(h[0], w)                      # the weight multiplies, per feature
+    # one-hot row: mean square v^2/K, so the live output is sign(v) * sqrt(K) * w_k
+    x = np.zeros((1, K), dtype=np.float16)
+    x[0, 77] = -0.5
+    h = prod.rmsnorm_f16(x, w, 0.0)
+    assert h[0, 77] == np.float16(-64.0 * np.float32(w[77])) and np.count_nonzero(h) == 1
+    # eps sits inside the square root, added to the MEAN of squares: c = 2, eps = 12 -> 1/sqrt(16)
+    h = prod.rmsnorm_f16(_f16(np.full((1, K), 2.0)), ones, 12.0)
+    assert np.all(h == np.float16(0.5))
+    # a zero row stays zero (no 0/0) once eps > 0
+    assert not np.any(prod.rmsnorm_f16(np.zeros((2, K), np.float16), w, 1e-6))
+
+
+def test_rmsnorm_scale_invariance_and_row_independence():
+    rng = np.random.default_rng(42)
+    x = _f16(rng.standard_normal((4, 512)))
+    w = _f16(1.0 + 0.1 * rng.standard_normal(512))
+    a = prod.rmsnorm_f16(x, w, 0.0)
+    b = prod.rmsnorm_f16(_f16(x.astype(np.float32) * 4.0), w, 0.0)     # exact scaling by a power of two
+    assert np.array_equal(a, b)
+    x2 = x.copy()
+    x2[2] = _f16(rng.standard_normal(512) * 9.0)
+    c = prod.rmsnorm_f16(x2, w, 0.0)
+    assert np.array_equal(a[[0, 1, 3]], c[[0, 1, 3]]) and not np.array_equal(a[2], c[2])
+
+
+def test_rmsnorm_vs_torch_cpu_float64():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(43)
+    x = _f16(rng.standard_normal((5, 1024)) * 3.0)
+    w = _f16(1.0 + 0.2 * rng.standard_normal(1024))
+    eps = 1e-5
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(x.astype(np.float64)), (1024,),
+                                       torch.from_numpy(w.astype(np.float64)), float(np.float32(eps))).numpy()
+    got = prod.rmsnorm_f16(x, w, eps).astype(np.float64)
+    # the oracle rounds twice (binary32, then fp16): at most one fp16 ulp from the real value, mostly exact
+    ulp = np.maximum(np.abs(ref), 2.0 ** -14) * 2.0 ** -10
+    assert np.all(np.abs(got - ref) <= 0.5001 * ulp + 1e-12)
+    assert np.mean(got == ref.astype(np.float16).astype(np.float64)) > 0.999
+
+
+def test_silu_mul_vs_high_precision_decimal():
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    gs = [0.0, 0.5, -0.5, 1.0986328125, -3.25, 7.0, -11.0, 20.0, -20.0, 60.0, 0.0001220703125, -65504.0]
+    us = [1.5, -2.25, 0.33349609375, 1.0, -7.0, 0.125, 3.0, -1.0, 2.0, 0.5, 1000.0, 1.0]
+    gu = _f16([gs + us])
+    got = prod.silu_mul_f16(gu)[0]
+    for i, (g, u) in enumerate(zip(gu[0, :len(gs)], gu[0, len(gs):])):
+        gd = Decimal(float(g))
+        s_exact = Fraction(gd / (1 + (-gd).exp())) if float(g) > -1000 else Fraction(0)
+        s32 = _fl(s_exact, 23, -126)
+        t32 = _fl(s32 * Fraction(float(u)), 23, -126)
+        assert Fraction(float(got[i])) == _fl(t32, 10, -14), (i, float(g), float(u))
+
+
+def test_silu_mul_closed_forms_and_column_order():
+    I = 256
+    rng = np.random.default_rng(44)
+    up = _f16(rng.standard_normal(I) * 2.0)
+    gate = _f16(rng.standard_normal(I) * 3.0)
+    # SiLU(0) = 0 whatever up holds
+    assert not np.any(prod.silu_mul_f16(np.concatenate([np.zeros(I, np.float16), up])[None, :]))
+    # large gate: SiLU is the identity in binary32, so h = fp16(g * u); gate is the FIRST half
+    big = _f16(np.full(I, 32.0))
+    h = prod.silu_mul_f16(np.concatenate([big, up])[None, :])[0]
+    assert np.array_equal(h, (np.float32(32.0) * up.astype(np.float32)).astype(np.float16))
+    h_swapped = prod.silu_mul_f16(np.concatenate([up, big])[None, :])[0]
+    assert not np.array_equal(h, h_swapped)
+    # SiLU(ln 3) = 0.75 ln 3 (sigmoid(ln 3) = 3/4), here through a gate that is fp16(ln 3)
+    g = np.float16(np.log(3.0))
+    sig = 1.0 / (1.0 + np.exp(-np.float64(g)))
+    h = prod.silu_mul_f16(_f16([[g, 1.0]]))[0, 0]
+    assert h == np.float16(np.float32(np.float64(g) * sig)) and abs(float(h) - 0.75 * np.log(3.0)) < 1e-3
+    # SiLU(g) - SiLU(-g) = g, to binary32 accuracy before the fp16 rounding: with up = 1 the two
+    # fp16 results differ by g within one fp16 ulp of the larger
+    ones = np.ones(I, np.float16)
+    p = prod.silu_mul_f16(np.concatenate([gate, ones])[None, :])[0].astype(np.float64)
+    n = prod.silu_mul_f16(np.concatenate([-gate, ones])[None, :])[0].astype(np.float64)
+    assert np.all(np.abs((p - n) - gate.astype(np.float64)) <= np.maximum(np.abs(p), np.abs(n)) * 2.0 ** -10 + 1e-7)
+
+
+def test_silu_mul_vs_torch_cpu_float64():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(45)
+    gu = _f16(rng.standard_normal((3, 2 * 384)) * 2.5)
+    g = torch.from_numpy(gu[:, :384].astype(np.float64))
+    u = torch.from_numpy(gu[:, 384:].astype(np.float64))
+    ref = (torch.nn.functional.silu(g) * u).numpy()
+    got = prod.silu_mul_f16(gu).astype(np.float64)
+    ulp = np.maximum(np.abs(ref), 2.0 ** -14) * 2.0 ** -10
+    assert np.all(np.abs(got - ref) <= 0.5001 * ulp + 1e-12)
+    assert np.mean(got == ref.astype(np.float16).astype(np.float64)) > 0.999
