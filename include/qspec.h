@@ -111,6 +111,27 @@ int qspec_quant_act(const void* x_f16, int M, int K, int group,
                     uint8_t* qa, float* sa, void* stream);
 
 /*
+ * Producers of draft-mode activations fused with the quantiser (paper Sec. 3.1,
+ * draft phase: every linear layer of the draft pass consumes 4-bit activations
+ * quantised on the fly; in a Llama-shaped block, Sec. 4.1, those activations
+ * come out of an RMSNorm or of SiLU(gate) * up).  One launch writes what
+ * qspec_quant_act would write for the fp16 tensor h the producer computes:
+ *   qspec_rmsnorm_quant:   r = fp32(1 / sqrt(sum_k x[m,k]^2 / K + eps))  (binary64 inside)
+ *                          h[m,k] = fp16(fp32((x[m,k] * w[k]) * r))
+ *   qspec_silu_mul_quant:  s = fp32(g / (1 + exp(-g)))                  (binary64 inside)
+ *                          h[m,i] = fp16(fp32(s * u)),  g = gate_up[m,i], u = gate_up[m,I+i]
+ *   x_f16       fp16 [M,K];  weight_f16 fp16 [K];  eps >= 0, finite;
+ *   gate_up_f16 fp16 [M,2I], the gate in the first I columns; I a positive multiple of 128;
+ *   qa, sa      out, as qspec_quant_act writes them for h ([M,K] resp. [M,I]);
+ *   h_f16       out, fp16 [M,K] resp. [M,I], or NULL when the tensor itself is not
+ *               needed (the draft pass needs only the codes).
+ */
+int qspec_rmsnorm_quant(const void* x_f16, const void* weight_f16, float eps, int M, int K, int group,
+                        uint8_t* qa, float* sa, void* h_f16, void* stream);
+int qspec_silu_mul_quant(const void* gate_up_f16, int M, int I, int group,
+                         uint8_t* qa, float* sa, void* h_f16, void* stream);
+
+/*
  * Draft-mode product (paper Sec. 1: W4A4 runs on the low-precision matrix
  * units without dequantising to a higher precision):
  *   P[m,n,j] = sum_{k in group j} qa[m,k] * qw[n,k]             (int32, exact)

@@ -20,6 +20,7 @@ EXPORTS = (
     "qspec_pack_weights", "qspec_unpack_weights", "qspec_quant_act", "qspec_gemm_w4a4",
     "qspec_gemm_w4a16", "qspec_gemm_w4a4_partials", "qspec_describe_kernel",
     "qspec_accept_workspace_bytes", "qspec_greedy_accept", "qspec_kv_overwrite",
+    "qspec_rmsnorm_quant", "qspec_silu_mul_quant",
 )
 
 
@@ -71,6 +72,10 @@ def lib() -> ctypes.CDLL:
     L.qspec_greedy_accept.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, sz, vp]
     L.qspec_kv_overwrite.restype = ci
     L.qspec_kv_overwrite.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+    L.qspec_rmsnorm_quant.restype = ci
+    L.qspec_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, ci, ci, ci, vp, vp, vp, vp]
+    L.qspec_silu_mul_quant.restype = ci
+    L.qspec_silu_mul_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -168,6 +173,43 @@ def quant_act(x: torch.Tensor, qa: torch.Tensor = None, sa: torch.Tensor = None,
                                  _dev(qa, torch.uint8, "qa"), _dev(sa, torch.float32, "sa"), _stream()),
            "qspec_quant_act")
     return qa, sa
+
+
+def _quant_outputs(M, K, group, device, qa, sa, h, want_h):
+    if qa is None:
+        qa = torch.empty((M, K // 2), dtype=torch.uint8, device=device)
+    if sa is None:
+        sa = torch.empty((M, max(K // group, 1)), dtype=torch.float32, device=device)
+    if h is None and want_h:
+        h = torch.empty((M, K), dtype=torch.float16, device=device)
+    return qa, sa, h
+
+
+def rmsnorm_quant(x: torch.Tensor, weight: torch.Tensor, eps: float, qa: torch.Tensor = None,
+                  sa: torch.Tensor = None, h: torch.Tensor = None, want_h: bool = False, group: int = GROUP):
+    """RMSNorm fused with the activation quantiser: x fp16 [M,K], weight fp16 [K] ->
+    (qa uint8 [M,K/2], sa fp32 [M,K/128], h fp16 [M,K] or None)."""
+    M, K = x.shape
+    qa, sa, h = _quant_outputs(M, K, group, x.device, qa, sa, h, want_h)
+    _check(lib().qspec_rmsnorm_quant(_dev(x, torch.float16, "x"), _dev(weight, torch.float16, "weight"),
+                                     float(eps), M, K, group, _dev(qa, torch.uint8, "qa"),
+                                     _dev(sa, torch.float32, "sa"),
+                                     None if h is None else _dev(h, torch.float16, "h"), _stream()),
+           "qspec_rmsnorm_quant")
+    return qa, sa, h
+
+
+def silu_mul_quant(gate_up: torch.Tensor, qa: torch.Tensor = None, sa: torch.Tensor = None,
+                   h: torch.Tensor = None, want_h: bool = False, group: int = GROUP):
+    """SiLU(gate) * up fused with the activation quantiser: gate_up fp16 [M,2I] (gate first) ->
+    (qa uint8 [M,I/2], sa fp32 [M,I/128], h fp16 [M,I] or None)."""
+    M, I = gate_up.shape[0], gate_up.shape[1] // 2
+    qa, sa, h = _quant_outputs(M, I, group, gate_up.device, qa, sa, h, want_h)
+    _check(lib().qspec_silu_mul_quant(_dev(gate_up, torch.float16, "gate_up"), M, I, group,
+                                      _dev(qa, torch.uint8, "qa"), _dev(sa, torch.float32, "sa"),
+                                      None if h is None else _dev(h, torch.float16, "h"), _stream()),
+           "qspec_silu_mul_quant")
+    return qa, sa, h
 
 
 def gemm_w4a4(packed: torch.Tensor, qa: torch.Tensor, sa: torch.Tensor, N: int,

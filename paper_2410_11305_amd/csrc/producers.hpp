@@ -1,0 +1,128 @@
+// The two producers of draft-mode activations in a Llama-shaped decoder block,
+// each fused with the activation quantiser that follows it in the draft pass
+// (paper Sec. 3.1, draft phase; Sec. 1: activations are quantised to 4 bit on
+// the fly): RMSNorm (input of the q/k/v and gate/up projections) and
+// SiLU(gate) * up (input of the down projection).  One launch instead of two
+// and no fp16 round trip through memory; the codes and scales are exactly the
+// quantiser's on the fp16 tensor the unfused producer would have written, and
+// that tensor can be written as well (the verify pass reads it).
+//
+// Arithmetic (fixed so that the codes are reproducible): the statistic and the
+// exponential in binary64, one binary32 rounding of everything that touches the
+// result, one rounding to fp16:
+//   RMSNorm:  r = fp32(1 / sqrt(sum(x^2) / K + eps)),  h = fp16(fp32((x * w) * r))
+//   SiLU*up:  s = fp32(g / (1 + exp(-g))),             h = fp16(fp32(s * u))
+// x * w is exact in binary32 (two 11-bit significands).  Both kernels are bound
+// by launch latency at draft sizes; the binary64 work is a few thousand
+// instructions per wavefront.
+#pragma once
+#include "common.hpp"
+#include "quant_act.hpp"
+
+namespace qspec {
+
+constexpr int kRowThreads = 256;
+constexpr int kRowChunk = kRowThreads * 8;        // features one pass of the workgroup covers
+
+// A binary32 value that exists as such: without this the compiler may merge the
+// multiplication with the conversion to fp16 that follows into one mixed-precision
+// instruction with a single rounding, which differs from the two roundings stated
+// above about once in 10^5 values.
+__device__ inline float rounded_f32(float v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
+__device__ inline double wave_sum_f64(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// grid M (one workgroup per token row), 256 threads.  NCH > 0: K <= NCH * 2048 and the
+// row stays in registers between the two passes; NCH == 0: any K, the row is read
+// again (from cache).  h_out may be null.
+template <int NCH>
+__global__ __launch_bounds__(kRowThreads) void rmsnorm_quant_kernel(const uint4* __restrict__ x,
+                                                                    const uint4* __restrict__ w, float eps, int K,
+                                                                    uint32_t* __restrict__ qa_words,
+                                                                    float* __restrict__ sa,
+                                                                    uint4* __restrict__ h_out) {
+  const int tid = threadIdx.x;
+  const int kw = K / 8;                                    // 16-byte pieces per row
+  const size_t row0 = (size_t)blockIdx.x * kw;
+  const int chunks = NCH > 0 ? NCH : (kw + kRowThreads - 1) / kRowThreads;
+  const uint4 zero = {0u, 0u, 0u, 0u};
+  uint4 keep[NCH > 0 ? NCH : 1];
+
+  double ss = 0.0;
+  for (int c = 0; c < chunks; ++c) {
+    const int piece = c * kRowThreads + tid;
+    const uint4 raw = piece < kw ? x[row0 + piece] : zero;
+    if (NCH > 0) keep[c] = raw;
+    const v8h h = __builtin_bit_cast(v8h, raw);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const double d = (double)(float)h[e];
+      ss += d * d;                                         // the square is exact
+    }
+  }
+  ss = wave_sum_f64(ss);
+  __shared__ double part[kRowThreads / 64];
+  if ((tid & 63) == 0) part[tid >> 6] = ss;
+  __syncthreads();
+  double total = part[0];
+#pragma unroll
+  for (int i = 1; i < kRowThreads / 64; ++i) total += part[i];
+  const float r = (float)(1.0 / sqrt(total / (double)K + (double)eps));
+
+  for (int c = 0; c < chunks; ++c) {
+    const int piece = c * kRowThreads + tid;
+    const bool live = piece < kw;
+    const uint4 raw = NCH > 0 ? keep[c] : (live ? x[row0 + piece] : zero);
+    const uint4 wraw = live ? w[piece] : zero;
+    const v8h xh = __builtin_bit_cast(v8h, raw);
+    const v8h wh = __builtin_bit_cast(v8h, wraw);
+    v8h hh;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float t = (float)xh[e] * (float)wh[e];         // exact
+      hh[e] = (_Float16)rounded_f32(t * r);
+      v[e] = (float)hh[e];
+    }
+    if (h_out != nullptr && live) h_out[row0 + piece] = __builtin_bit_cast(uint4, hh);
+    quantise_unit(v, live, row0 + piece, qa_words, sa);
+  }
+}
+
+// gate_up: fp16 [M][2I], the gate in the first I columns.  One thread per 8 outputs,
+// n_words = M * I / 8.  h_out may be null.
+__global__ __launch_bounds__(256) void silu_mul_quant_kernel(const uint4* __restrict__ gate_up, int I8,
+                                                             uint32_t* __restrict__ qa_words,
+                                                             float* __restrict__ sa, uint4* __restrict__ h_out,
+                                                             size_t n_words) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool live = idx < n_words;
+  uint4 graw = {0u, 0u, 0u, 0u}, uraw = {0u, 0u, 0u, 0u};
+  if (live) {
+    const size_t m = idx / (size_t)I8, p = idx - m * (size_t)I8;
+    graw = gate_up[m * 2 * (size_t)I8 + p];
+    uraw = gate_up[m * 2 * (size_t)I8 + (size_t)I8 + p];
+  }
+  const v8h gh = __builtin_bit_cast(v8h, graw);
+  const v8h uh = __builtin_bit_cast(v8h, uraw);
+  v8h hh;
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const double g = (double)(float)gh[e];
+    const float s = (float)(g / (1.0 + exp(-g)));
+    hh[e] = (_Float16)rounded_f32(s * (float)uh[e]);
+    v[e] = (float)hh[e];
+  }
+  if (h_out != nullptr && live) h_out[idx] = __builtin_bit_cast(uint4, hh);
+  quantise_unit(v, live, idx, qa_words, sa);
+}
+
+}  // namespace qspec

@@ -15,6 +15,7 @@
 #include "gemm_tile16.hpp"
 #include "gemm_tile4.hpp"
 #include "pack.hpp"
+#include "producers.hpp"
 #include "quant_act.hpp"
 
 using namespace qspec;
@@ -485,6 +486,42 @@ int qspec_quant_act(const void* x_f16, int M, int K, int group, uint8_t* qa, flo
   hipLaunchKernelGGL(quant_act_kernel, dim3(blocks_for(n_words, 256)), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint4*>(x_f16),
                      reinterpret_cast<uint32_t*>(qa), sa, n_words);
+  return launch_status();
+}
+
+int qspec_rmsnorm_quant(const void* x_f16, const void* weight_f16, float eps, int M, int K, int group,
+                        uint8_t* qa, float* sa, void* h_f16, void* stream) {
+  if (!x_f16 || !weight_f16 || !qa || !sa) return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, kTileRows, K, group)) return st;
+  if (!(eps >= 0.0f) || !(eps <= 3.0e38f)) return QSPEC_ERR_SHAPE;
+  if (misaligned(x_f16) || misaligned(weight_f16) || misaligned(qa) || misaligned(sa) || misaligned(h_f16))
+    return QSPEC_ERR_ALIGN;
+  if (int st = check_device()) return st;
+  const hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint4* x = static_cast<const uint4*>(x_f16);
+  const uint4* w = static_cast<const uint4*>(weight_f16);
+  uint32_t* words = reinterpret_cast<uint32_t*>(qa);
+  uint4* h = static_cast<uint4*>(h_f16);
+  const int chunks = (K + kRowChunk - 1) / kRowChunk;
+  const dim3 grid(M), block(kRowThreads);
+  if (chunks <= 1) hipLaunchKernelGGL(rmsnorm_quant_kernel<1>, grid, block, 0, s, x, w, eps, K, words, sa, h);
+  else if (chunks <= 2) hipLaunchKernelGGL(rmsnorm_quant_kernel<2>, grid, block, 0, s, x, w, eps, K, words, sa, h);
+  else if (chunks <= 4) hipLaunchKernelGGL(rmsnorm_quant_kernel<4>, grid, block, 0, s, x, w, eps, K, words, sa, h);
+  else if (chunks <= 8) hipLaunchKernelGGL(rmsnorm_quant_kernel<8>, grid, block, 0, s, x, w, eps, K, words, sa, h);
+  else hipLaunchKernelGGL(rmsnorm_quant_kernel<0>, grid, block, 0, s, x, w, eps, K, words, sa, h);
+  return launch_status();
+}
+
+int qspec_silu_mul_quant(const void* gate_up_f16, int M, int I, int group,
+                         uint8_t* qa, float* sa, void* h_f16, void* stream) {
+  if (!gate_up_f16 || !qa || !sa) return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, kTileRows, I, group)) return st;
+  if (misaligned(gate_up_f16) || misaligned(qa) || misaligned(sa) || misaligned(h_f16)) return QSPEC_ERR_ALIGN;
+  if (int st = check_device()) return st;
+  const size_t n_words = (size_t)M * I / 8;
+  hipLaunchKernelGGL(silu_mul_quant_kernel, dim3(blocks_for(n_words, 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(gate_up_f16), I / 8,
+                     reinterpret_cast<uint32_t*>(qa), sa, static_cast<uint4*>(h_f16), n_words);
   return launch_status();
 }
 

@@ -10,22 +10,14 @@ namespace qspec {
 // One thread owns 8 consecutive activations (one 16-byte load, one 32-bit
 // code word); 16 adjacent lanes own one group, so the absmax is a 4-step
 // butterfly inside a quarter wavefront and no LDS is needed.
-__global__ __launch_bounds__(256) void quant_act_kernel(const uint4* __restrict__ x,
-                                                        uint32_t* __restrict__ qa_words,
-                                                        float* __restrict__ sa,
-                                                        size_t n_words) {
-  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  // n_words is a multiple of 16, so a 16-lane group is entirely in or out of
-  // range; out-of-range lanes still take part in the shuffles below.
-  const bool live = idx < n_words;
-  uint4 raw = {0u, 0u, 0u, 0u};
-  if (live) raw = x[idx];
-  float v[8];
-  {
-    const v8h h = __builtin_bit_cast(v8h, raw);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = (float)h[e];
-  }
+//
+// quantise_unit: v = this thread's 8 activations (fp16 values widened to
+// binary32), idx = index of its code word in the [M][K/8] word array.  Every lane
+// of the wavefront must call it (the shuffles); lanes that are not `live` pass
+// zeros and store nothing.  The number of words per row is a multiple of 16, so
+// a 16-lane group is entirely live or not.
+__device__ inline void quantise_unit(const float (&v)[8], bool live, size_t idx,
+                                     uint32_t* __restrict__ qa_words, float* __restrict__ sa) {
   float a = 0.0f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(v[e]));
@@ -48,6 +40,23 @@ __global__ __launch_bounds__(256) void quant_act_kernel(const uint4* __restrict_
     qa_words[(idx & ~(size_t)15) + ((kw & 3) << 2) + (kw >> 2)] = w;
     if ((threadIdx.x & 15) == 0) sa[idx >> 4] = s;
   }
+}
+
+__global__ __launch_bounds__(256) void quant_act_kernel(const uint4* __restrict__ x,
+                                                        uint32_t* __restrict__ qa_words,
+                                                        float* __restrict__ sa,
+                                                        size_t n_words) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool live = idx < n_words;
+  uint4 raw = {0u, 0u, 0u, 0u};
+  if (live) raw = x[idx];
+  float v[8];
+  {
+    const v8h h = __builtin_bit_cast(v8h, raw);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)h[e];
+  }
+  quantise_unit(v, live, idx, qa_words, sa);
 }
 
 }  // namespace qspec

@@ -20,6 +20,9 @@ Inputs of the steps after the verify pass (accept_case): stream 5 of a config,
   drafts   the planted token of their row with probability p_accept, else another id
   V is the Llama vocabulary size of the config's model class (32000; 128256 exists
   in the Llama-3 checkpoints the paper also serves and is covered by the tests).
+Inputs of the fused producers (producer_case): the residual stream x as above
+  (N(0,1), outlier channels x20), an RMSNorm weight 1 + 0.1 N(0,1) -> fp16, and a merged
+  gate/up tensor N(0, 1.5) -> fp16 [M, 2I]; eps = 1e-5 (the Llama-2 value).
 """
 from __future__ import annotations
 
@@ -146,3 +149,26 @@ def accept_case(seed: int, B: int, gamma: int, V: int, p_accept: float = 0.8):
 def accept_inputs(config: int):
     cfg = CONFIGS[config]
     return accept_case(_seed(config, 0, 5), cfg.batch, cfg.gamma, VOCAB[config])
+
+
+RMS_EPS = 1e-5
+
+
+def producer_case(seed: int, M: int, K: int, I: int, outlier_frac: float = 0.01):
+    """Inputs of the fused producers: returns (x fp16 [M, K], norm weight fp16 [K],
+    gate_up fp16 [M, 2I])."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K), dtype=np.float32)
+    n_out = max(1, int(round(outlier_frac * K)))
+    x[:, rng.choice(K, size=n_out, replace=False)] *= np.float32(20.0)
+    w = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float16)
+    gate_up = (rng.standard_normal((M, 2 * I), dtype=np.float32) * np.float32(1.5)).astype(np.float16)
+    return x.astype(np.float16), w, gate_up
+
+
+def producer_inputs(config: int):
+    """Draft-pass producer inputs of a configuration: hidden size = K of its first layer,
+    intermediate size = K of its last layer (the down projection)."""
+    cfg = CONFIGS[config]
+    K, I = cfg.layers[0].K, cfg.layers[-1].K
+    return producer_case(_seed(config, 0, 6), cfg.draft_M, K, I)

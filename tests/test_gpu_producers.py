@@ -1,0 +1,134 @@
+"""GPU-vs-oracle parity of the producers fused with the activation quantiser
+(RMSNorm, SiLU(gate) * up; the draft phase of paper Sec. 3.1 consumes their
+output as 4-bit codes) through the C ABI.  The arithmetic is fixed on both
+sides, so the fp16 tensor, the codes and the scales must match bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import device_layout as lay
+from oracle import producers_oracle as prod
+from oracle import qspec_oracle as orc
+from paper_2410_11305_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2410_11305_amd import binding as B
+    assert torch.cuda.is_available()
+    B.lib()
+    return torch, B
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_against(torch, qa, sa, h, h_ref):
+    """The fused launch must equal the oracle's quantiser applied to the oracle's fp16 tensor."""
+    q_ref, s_ref = orc.quant_act(h_ref)
+    torch.cuda.synchronize()
+    if h is not None:
+        assert np.array_equal(h.cpu().numpy().view(np.uint16), h_ref.view(np.uint16))
+    assert np.array_equal(sa.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(qa.cpu().numpy(), lay.act_bytes(q_ref))
+
+
+def run_rmsnorm(env, x, w, eps, want_h=True):
+    torch, B = env
+    qa, sa, h = B.rmsnorm_quant(dev(torch, x), dev(torch, w), eps, want_h=want_h)
+    check_against(torch, qa, sa, h, prod.rmsnorm_f16(x, w, eps))
+    return qa, sa
+
+
+def run_silu(env, gu, want_h=True):
+    torch, B = env
+    qa, sa, h = B.silu_mul_quant(dev(torch, gu), want_h=want_h)
+    check_against(torch, qa, sa, h, prod.silu_mul_f16(gu))
+    return qa, sa
+
+
+# K: one partial chunk, exactly one chunk, ragged second chunk, the hidden sizes of the
+# configurations, more than the register-resident limit (16384) with a ragged tail
+@pytest.mark.parametrize("M,K", [(1, 128), (3, 256), (5, 2048), (4, 2176), (8, 4096), (64, 5120), (128, 8192),
+                                 (2, 16384), (3, 16512), (2, 28672), (300, 384)])
+def test_rmsnorm_quant_bit_exact(env, M, K):
+    x, w, _ = synth.producer_case(300 + M + K, M, K, 128)
+    run_rmsnorm(env, x, w, synth.RMS_EPS)
+    run_rmsnorm(env, x, w, synth.RMS_EPS, want_h=False)
+
+
+def test_rmsnorm_quant_special_rows(env):
+    K = 512
+    rng = np.random.default_rng(7)
+    x = np.zeros((7, K), dtype=np.float16)
+    x[1] = 3.0                                              # constant row
+    x[2, 77] = -0.5                                         # one-hot
+    x[3] = rng.standard_normal(K) * 6e-5                    # fp16 subnormals, eps dominates
+    x[4] = rng.standard_normal(K) * 2000.0                  # large magnitudes
+    x[5, :128] = rng.standard_normal(128)                   # three all-zero groups
+    x[6] = rng.standard_normal(K)
+    w = (1.0 + 0.25 * rng.standard_normal(K)).astype(np.float16)
+    for eps in (1e-6, 1e-5, 12.0):
+        run_rmsnorm(env, x, w, eps)
+    run_rmsnorm(env, x[1:3], w, 0.0)                        # eps = 0 on rows that are not zero
+
+
+@pytest.mark.parametrize("M,I", [(1, 128), (3, 384), (8, 11008), (64, 13824), (128, 28672), (515, 256)])
+def test_silu_mul_quant_bit_exact(env, M, I):
+    _, _, gu = synth.producer_case(400 + M + I, M, 128, I)
+    run_silu(env, gu)
+    run_silu(env, gu, want_h=False)
+
+
+def test_silu_mul_quant_whole_gate_range(env):
+    """Every finite fp16 bit pattern as a gate value (both signs), against a few up values."""
+    bits = np.concatenate([np.arange(0, 0x7C00, dtype=np.uint16), np.arange(0x8000, 0xFC00, dtype=np.uint16)])
+    gate = np.resize(bits.view(np.float16), (62, 1024))
+    rng = np.random.default_rng(8)
+    up = np.resize(np.array([1.0, -0.5, 0.001, 0.75], np.float16), (62, 1024)) * \
+        rng.choice(np.array([1, 1, 0.5], np.float16), size=(62, 1024))
+    gu = np.concatenate([gate, up.astype(np.float16)], axis=1)
+    with np.errstate(over="ignore", invalid="ignore"):
+        h_ref = prod.silu_mul_f16(gu)
+    finite = np.isfinite(h_ref.astype(np.float32)).all(axis=1)      # fp16 overflow of g * u is out of contract
+    run_silu(env, gu[finite])
+
+
+@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
+def test_producers_on_benchmark_shapes_feed_the_draft_gemm(env, config):
+    """Draft-pass shapes of every configuration; the codes of the fused RMSNorm go
+    through the draft-mode GEMM of the first layer and must give what the quantiser's
+    own codes give (same bytes in, same kernel)."""
+    torch, B = env
+    x, w, gu = synth.producer_inputs(config)
+    qa, sa = run_rmsnorm(env, x, w, synth.RMS_EPS)
+    run_silu(env, gu)
+    layer = synth.CONFIGS[config].layers[0]
+    N = min(layer.N, 1024)
+    codes = synth.weight_codes(config, 0, layer.N, layer.K)[:N]
+    scales = synth.weight_scales(config, 0, layer.N, layer.K)[:N]
+    blob = B.pack_weights(dev(torch, codes), dev(torch, scales))
+    h = dev(torch, prod.rmsnorm_f16(x, w, synth.RMS_EPS))
+    qa2, sa2 = B.quant_act(h)
+    y1 = B.gemm_w4a4(blob, qa, sa, N)
+    y2 = B.gemm_w4a4(blob, qa2, sa2, N)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
+
+
+def test_bad_arguments_are_refused(env):
+    torch, B = env
+    x = torch.zeros((2, 256), dtype=torch.float16, device="cuda")
+    w = torch.ones((256,), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.QSpecError):
+        B.rmsnorm_quant(x, w, -1.0)
+    with pytest.raises(B.QSpecError):
+        B.rmsnorm_quant(x, w, float("nan"))
+    with pytest.raises(B.QSpecError):
+        B.rmsnorm_quant(x[:, :192].contiguous(), w[:192].contiguous(), 1e-5)      # K not a multiple of 128
+    with pytest.raises(B.QSpecError):
+        B.silu_mul_quant(torch.zeros((2, 2 * 192), dtype=torch.float16, device="cuda"))
+    torch.cuda.synchronize()
