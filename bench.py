@@ -335,6 +335,38 @@ def main() -> int:
                        reps, 2) / n_rep_small
     acc_bytes = Bn * rows * V * 2 + Bn * (rows - 1) * 4 + Bn * (rows + 1) * 4
     kv_bytes = int((n_acc.sum().item() + Bn) * kvD * 2 * 2)
+    # ---- the fused producers of draft-mode activations (RMSNorm + quantiser, SiLU*up +
+    # quantiser): beside the step as well, against the quantiser alone on the same shape
+    # and against the unfused pair with torch's own producer kernels in front of it
+    px_h, pw_h, pgu_h = synth.producer_inputs(args.config)
+    px, pw, pgu = to(px_h), to(pw_h), to(pgu_h)
+    Kh, Ii = px.shape[1], pgu.shape[1] // 2
+    pq_h = (torch.empty((Md, Kh // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Kh // 128), dtype=torch.float32, device=dev))
+    pq_i = (torch.empty((Md, Ii // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Ii // 128), dtype=torch.float32, device=dev))
+    ph = torch.empty((Md, Kh), dtype=torch.float16, device=dev)
+    pi = torch.empty((Md, Ii), dtype=torch.float16, device=dev)
+
+    def torch_rms():
+        return torch.nn.functional.rms_norm(px, (Kh,), pw, synth.RMS_EPS)
+
+    def torch_silu():
+        return torch.nn.functional.silu(pgu[:, :Ii]) * pgu[:, Ii:]
+
+    def per_call(f):
+        return time_runner(make_runner(lambda: [f() for _ in range(n_rep_small)]), reps, 2) / n_rep_small * 1e6
+
+    fused_producers = {
+        "M": Md, "hidden": Kh, "intermediate": Ii,
+        "rmsnorm_quant_us": round(per_call(lambda: B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1])), 3),
+        "quant_act_alone_hidden_us": round(per_call(lambda: B.quant_act(ph, pq_h[0], pq_h[1])), 3),
+        "torch_rms_norm_then_quant_act_us": round(per_call(lambda: B.quant_act(torch_rms(), pq_h[0], pq_h[1])), 3),
+        "silu_mul_quant_us": round(per_call(lambda: B.silu_mul_quant(pgu, pq_i[0], pq_i[1])), 3),
+        "quant_act_alone_intermediate_us": round(per_call(lambda: B.quant_act(pi, pq_i[0], pq_i[1])), 3),
+        "torch_silu_mul_then_quant_act_us": round(per_call(lambda: B.quant_act(torch_silu(), pq_i[0], pq_i[1])), 3),
+    }
+    fused_producers["silu_mul_quant_GBps"] = round((Md * Ii * 4 + Md * Ii // 2 + Md * (Ii // 128) * 4)
+                                                   / fused_producers["silu_mul_quant_us"] / 1e3, 1)
+
     after_verify = {
         "greedy_accept": dict(B=Bn, gamma=rows - 1, V=V, us=round(t_acc * 1e6, 3), launches=2,
                               GBps=round(acc_bytes / t_acc / 1e9, 1), hbm_frac=round(acc_bytes / t_acc / 1e9 / HBM_PEAK_GBS, 4),
@@ -403,6 +435,7 @@ def main() -> int:
                        "w4a16_at_draft_M_pass_us": None if t_16d is None else round(t_16d * 1e6, 1)},
         "pack_weights_GBps": round(pack_bytes / t_pack / 1e9, 1) if t_pack > 0 else None,
         "after_verify": after_verify,
+        "fused_producers": fused_producers,
         "extra_rows_M256_M512": extra,
         "vendor_fp16_gemm_context": vendor,
     }

@@ -21,8 +21,7 @@
 
 namespace qspec {
 
-constexpr int kRowThreads = 256;
-constexpr int kRowChunk = kRowThreads * 8;        // features one pass of the workgroup covers
+constexpr int kRowMaxThreads = 1024;
 
 // A binary32 value that exists as such: without this the compiler may merge the
 // multiplication with the conversion to fp16 that follows into one mixed-precision
@@ -33,33 +32,72 @@ __device__ inline float rounded_f32(float v) {
   return v;
 }
 
-__device__ inline double wave_sum_f64(double v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
+template <int CTRL>
+__device__ inline double dpp_f64(double v) {
+  const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+  const unsigned lo = (unsigned)dpp_i32<CTRL>((int)(unsigned)b);
+  const unsigned hi = (unsigned)dpp_i32<CTRL>((int)(unsigned)(b >> 32));
+  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
 }
 
-// grid M (one workgroup per token row), 256 threads.  NCH > 0: K <= NCH * 2048 and the
-// row stays in registers between the two passes; NCH == 0: any K, the row is read
-// again (from cache).  h_out may be null.
+__device__ inline double lane_value_f64(double v, int lane) {
+  const unsigned long long b = __builtin_bit_cast(unsigned long long, v);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, lane);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), lane);
+  return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+// Sum over the wavefront (every lane active), the same value in every lane: four folds
+// inside each row of 16, then the four row totals.
+__device__ inline double wave_sum_f64(double v) {
+  v += dpp_f64<0xB1>(v);
+  v += dpp_f64<0x4E>(v);
+  v += dpp_f64<0x141>(v);
+  v += dpp_f64<0x140>(v);
+  return (lane_value_f64(v, 0) + lane_value_f64(v, 16)) + (lane_value_f64(v, 32) + lane_value_f64(v, 48));
+}
+
+// 1/sqrt(v) in binary64 to within a few units in the last place, v > 0 and normal: the
+// hardware estimate and three Newton steps (each squares the relative error), instead of
+// the correctly rounded square root and division, whose long dependent chains would sit
+// on this kernel's critical path.  The result is rounded to binary32 straight away.
+__device__ inline double rsqrt_f64(double v) {
+  double y = __builtin_amdgcn_rsq(v);
+#pragma unroll
+  for (int it = 0; it < 3; ++it) {
+    const double e = fma(-v * y, y, 1.0);                  // 1 - v y^2
+    y = fma(y * 0.5, e, y);                                // y (1 + e/2)
+  }
+  return y;
+}
+
+// grid M (one workgroup per token row), T = blockDim.x threads (a multiple of 64, at most
+// 1024), 8 features per thread and pass.  NCH > 0: K <= NCH * 8 T and the row (and the norm
+// weight) stay in registers between the two passes; NCH == 0: any K, the row is read again
+// (from cache).  inv_K = 1 / K.  h_out may be null.
 template <int NCH>
-__global__ __launch_bounds__(kRowThreads) void rmsnorm_quant_kernel(const uint4* __restrict__ x,
-                                                                    const uint4* __restrict__ w, float eps, int K,
-                                                                    uint32_t* __restrict__ qa_words,
-                                                                    float* __restrict__ sa,
-                                                                    uint4* __restrict__ h_out) {
-  const int tid = threadIdx.x;
+__global__ __launch_bounds__(kRowMaxThreads) void rmsnorm_quant_kernel(const uint4* __restrict__ x,
+                                                                       const uint4* __restrict__ w, float eps,
+                                                                       int K, double inv_K,
+                                                                       uint32_t* __restrict__ qa_words,
+                                                                       float* __restrict__ sa,
+                                                                       uint4* __restrict__ h_out) {
+  const int tid = threadIdx.x, T = blockDim.x;
   const int kw = K / 8;                                    // 16-byte pieces per row
   const size_t row0 = (size_t)blockIdx.x * kw;
-  const int chunks = NCH > 0 ? NCH : (kw + kRowThreads - 1) / kRowThreads;
+  const int chunks = NCH > 0 ? NCH : (kw + T - 1) / T;
   const uint4 zero = {0u, 0u, 0u, 0u};
-  uint4 keep[NCH > 0 ? NCH : 1];
+  uint4 keep[NCH > 0 ? NCH : 1], wkeep[NCH > 0 ? NCH : 1];
 
   double ss = 0.0;
+#pragma unroll
   for (int c = 0; c < chunks; ++c) {
-    const int piece = c * kRowThreads + tid;
+    const int piece = c * T + tid;
     const uint4 raw = piece < kw ? x[row0 + piece] : zero;
-    if (NCH > 0) keep[c] = raw;
+    if (NCH > 0) {
+      keep[c] = raw;
+      wkeep[c] = piece < kw ? w[piece] : zero;             // in flight during the reduction
+    }
     const v8h h = __builtin_bit_cast(v8h, raw);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -68,31 +106,33 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_quant_kernel(const uint4*
     }
   }
   ss = wave_sum_f64(ss);
-  __shared__ double part[kRowThreads / 64];
+  __shared__ double part[kRowMaxThreads / 64];
   if ((tid & 63) == 0) part[tid >> 6] = ss;
   __syncthreads();
   double total = part[0];
-#pragma unroll
-  for (int i = 1; i < kRowThreads / 64; ++i) total += part[i];
-  const float r = (float)(1.0 / sqrt(total / (double)K + (double)eps));
+  for (int i = 1; i < (T >> 6); ++i) total += part[i];
+  const double v = total * inv_K + (double)eps;
+  // v == 0 only for a zero row with eps == 0: the outputs are 0 * r, and r = inf would make them NaN
+  const float r = v > 0.0 ? (float)rsqrt_f64(v) : 0.0f;
 
+#pragma unroll
   for (int c = 0; c < chunks; ++c) {
-    const int piece = c * kRowThreads + tid;
+    const int piece = c * T + tid;
     const bool live = piece < kw;
     const uint4 raw = NCH > 0 ? keep[c] : (live ? x[row0 + piece] : zero);
-    const uint4 wraw = live ? w[piece] : zero;
+    const uint4 wraw = NCH > 0 ? wkeep[c] : (live ? w[piece] : zero);
     const v8h xh = __builtin_bit_cast(v8h, raw);
     const v8h wh = __builtin_bit_cast(v8h, wraw);
     v8h hh;
-    float v[8];
+    float v8[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float t = (float)xh[e] * (float)wh[e];         // exact
       hh[e] = (_Float16)rounded_f32(t * r);
-      v[e] = (float)hh[e];
+      v8[e] = (float)hh[e];
     }
     if (h_out != nullptr && live) h_out[row0 + piece] = __builtin_bit_cast(uint4, hh);
-    quantise_unit(v, live, row0 + piece, qa_words, sa);
+    quantise_unit(v8, live, row0 + piece, qa_words, sa);
   }
 }
 

@@ -502,13 +502,16 @@ int qspec_rmsnorm_quant(const void* x_f16, const void* weight_f16, float eps, in
   const uint4* w = static_cast<const uint4*>(weight_f16);
   uint32_t* words = reinterpret_cast<uint32_t*>(qa);
   uint4* h = static_cast<uint4*>(h_f16);
-  const int chunks = (K + kRowChunk - 1) / kRowChunk;
-  const dim3 grid(M), block(kRowThreads);
-  if (chunks <= 1) hipLaunchKernelGGL(rmsnorm_quant_kernel<1>, grid, block, 0, s, x, w, eps, K, words, sa, h);
-  else if (chunks <= 2) hipLaunchKernelGGL(rmsnorm_quant_kernel<2>, grid, block, 0, s, x, w, eps, K, words, sa, h);
-  else if (chunks <= 4) hipLaunchKernelGGL(rmsnorm_quant_kernel<4>, grid, block, 0, s, x, w, eps, K, words, sa, h);
-  else if (chunks <= 8) hipLaunchKernelGGL(rmsnorm_quant_kernel<8>, grid, block, 0, s, x, w, eps, K, words, sa, h);
-  else hipLaunchKernelGGL(rmsnorm_quant_kernel<0>, grid, block, 0, s, x, w, eps, K, words, sa, h);
+  // threads per row: one per 8 features up to 1024, whole wavefronts
+  const int kw = K / 8;
+  const int T = kw >= kRowMaxThreads ? kRowMaxThreads : (kw + 63) / 64 * 64;
+  const int chunks = (kw + T - 1) / T;
+  const double inv_K = 1.0 / (double)K;
+  const dim3 grid(M), block(T);
+  if (chunks <= 1) hipLaunchKernelGGL(rmsnorm_quant_kernel<1>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h);
+  else if (chunks <= 2) hipLaunchKernelGGL(rmsnorm_quant_kernel<2>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h);
+  else if (chunks <= 4) hipLaunchKernelGGL(rmsnorm_quant_kernel<4>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h);
+  else hipLaunchKernelGGL(rmsnorm_quant_kernel<0>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h);
   return launch_status();
 }
 

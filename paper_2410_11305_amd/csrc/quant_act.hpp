@@ -7,9 +7,27 @@
 
 namespace qspec {
 
+// Data-parallel-primitive moves inside a row of 16 lanes: lane i reads its partner in
+// the quad (0xB1: i^1, 0x4E: i^2), in its half row (0x141: 7 - i) or in the row
+// (0x140: 15 - i).  Four of them in this order fold a row of 16; they run in the
+// vector ALU, where a cross-lane shuffle takes a round trip through the LDS crossbar.
+// Every lane of the row must be active.
+template <int CTRL>
+__device__ inline int dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+
+__device__ inline float row16_max(float a) {
+  a = fmaxf(a, __builtin_bit_cast(float, dpp_i32<0xB1>(__builtin_bit_cast(int, a))));
+  a = fmaxf(a, __builtin_bit_cast(float, dpp_i32<0x4E>(__builtin_bit_cast(int, a))));
+  a = fmaxf(a, __builtin_bit_cast(float, dpp_i32<0x141>(__builtin_bit_cast(int, a))));
+  a = fmaxf(a, __builtin_bit_cast(float, dpp_i32<0x140>(__builtin_bit_cast(int, a))));
+  return a;
+}
+
 // One thread owns 8 consecutive activations (one 16-byte load, one 32-bit
-// code word); 16 adjacent lanes own one group, so the absmax is a 4-step
-// butterfly inside a quarter wavefront and no LDS is needed.
+// code word); 16 adjacent lanes (one row) own one group, so the absmax is a
+// 4-step fold inside the row and no LDS is needed.
 //
 // quantise_unit: v = this thread's 8 activations (fp16 values widened to
 // binary32), idx = index of its code word in the [M][K/8] word array.  Every lane
@@ -21,8 +39,7 @@ __device__ inline void quantise_unit(const float (&v)[8], bool live, size_t idx,
   float a = 0.0f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(v[e]));
-#pragma unroll
-  for (int off = 1; off < 16; off <<= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+  a = row16_max(a);
   const float s = a / 7.0f;
   uint32_t w = 0;
   if (a > 0.0f) {

@@ -50,10 +50,11 @@ def run_silu(env, gu, want_h=True):
     return qa, sa
 
 
-# K: one partial chunk, exactly one chunk, ragged second chunk, the hidden sizes of the
-# configurations, more than the register-resident limit (16384) with a ragged tail
+# K: less than a wavefront's worth, ragged last wavefront, the hidden sizes of the
+# configurations (one pass of up to 1024 threads), two and four passes with ragged tails,
+# and more than the register-resident limit (32768)
 @pytest.mark.parametrize("M,K", [(1, 128), (3, 256), (5, 2048), (4, 2176), (8, 4096), (64, 5120), (128, 8192),
-                                 (2, 16384), (3, 16512), (2, 28672), (300, 384)])
+                                 (2, 16384), (3, 16512), (2, 28672), (2, 33024), (300, 384)])
 def test_rmsnorm_quant_bit_exact(env, M, K):
     x, w, _ = synth.producer_case(300 + M + K, M, K, 128)
     run_rmsnorm(env, x, w, synth.RMS_EPS)
