@@ -120,7 +120,8 @@ int qspec_quant_act(const void* x_f16, int M, int K, int group,
  *                          h[m,k] = fp16(fp32((x[m,k] * w[k]) * r))
  *   qspec_silu_mul_quant:  s = fp32(g / (1 + exp(-g)))                  (binary64 inside)
  *                          h[m,i] = fp16(fp32(s * u)),  g = gate_up[m,i], u = gate_up[m,I+i]
- *   x_f16       fp16 [M,K];  weight_f16 fp16 [K];  eps >= 0, finite;
+ *   x_f16       fp16 [M,K];  weight_f16 fp16 [K];  eps >= 0, finite (an all-zero row with
+ *               eps = 0 gives zeros);
  *   gate_up_f16 fp16 [M,2I], the gate in the first I columns; I a positive multiple of 128;
  *   qa, sa      out, as qspec_quant_act writes them for h ([M,K] resp. [M,I]);
  *   h_f16       out, fp16 [M,K] resp. [M,I], or NULL when the tensor itself is not

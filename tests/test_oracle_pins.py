@@ -690,3 +690,74 @@ def test_silu_mul_vs_torch_cpu_float64():
     ulp = np.maximum(np.abs(ref), 2.0 ** -14) * 2.0 ** -10
     assert np.all(np.abs(got - ref) <= 0.5001 * ulp + 1e-12)
     assert np.mean(got == ref.astype(np.float16).astype(np.float64)) > 0.999
+
+
+# ---------------------------------------------------------------- rotation in front of the quantiser
+from oracle import rotation_oracle as rot
+
+
+def _h128():
+    from scipy.linalg import hadamard
+    return hadamard(128).astype(np.float64)
+
+
+def test_hadamard_equals_the_matrix_product_where_sums_are_exact():
+    rng = np.random.default_rng(51)
+    x = rng.integers(-40, 41, size=(5, 384)).astype(np.float16)          # small integers: every partial sum is exact
+    x[4] *= np.float16(0.25)                                             # and a row of quarter-integers
+    got = rot.hadamard128_f16(x)
+    ref = (x.astype(np.float64).reshape(5, 3, 128) @ _h128() / 8.0).reshape(5, 384)
+    assert np.array_equal(got.astype(np.float64), ref.astype(np.float16).astype(np.float64))
+    assert np.abs(ref).max() > 100                                       # not a trivial case
+
+
+def test_hadamard_entries_on_one_hot_rows():
+    x = np.zeros((128, 128), dtype=np.float16)
+    x[np.arange(128), np.arange(128)] = 8.0
+    got = rot.hadamard128_f16(x).astype(np.int64)
+    for i in (0, 1, 2, 3, 64, 85, 127):
+        for j in range(128):
+            assert got[i, j] == (-1) ** bin(i & j).count("1")
+    assert np.array_equal(got, got.T) and np.array_equal(got @ got.T, 128 * np.eye(128, dtype=np.int64))
+
+
+def test_hadamard_groups_are_independent_and_twice_is_doubling():
+    rng = np.random.default_rng(52)
+    x = rng.integers(-6, 7, size=(3, 256)).astype(np.float16)
+    once = rot.hadamard128_f16(x)
+    twice = rot.hadamard128_f16(once)                                    # (1/8)(1/8) H H = 2 I, exact on these inputs
+    assert np.array_equal(twice.astype(np.float32), 2.0 * x.astype(np.float32))
+    x2 = x.copy()
+    x2[:, 128:] = rng.integers(-6, 7, size=(3, 128)).astype(np.float16)
+    assert np.array_equal(rot.hadamard128_f16(x2)[:, :128], once[:, :128])
+
+
+def test_hadamard_general_inputs_close_to_float64_and_energy_kept():
+    rng = np.random.default_rng(53)
+    x = (rng.standard_normal((4, 512)) * 3.0).astype(np.float16)
+    x[:, 7] *= 20
+    got = rot.hadamard128_f16(x).astype(np.float64)
+    ref = (x.astype(np.float64).reshape(4, 4, 128) @ _h128() / 8.0).reshape(4, 512)
+    assert np.all(np.abs(got - ref) <= np.maximum(np.abs(ref), 1e-3) * 2.0 ** -10)
+    e_in = (x.astype(np.float64) ** 2).reshape(4, 4, 128).sum(-1)
+    e_out = (got ** 2).reshape(4, 4, 128).sum(-1)
+    assert np.allclose(e_out, 2.0 * e_in, rtol=2e-3)                     # |x H / 8|^2 = 128 / 64 |x|^2
+
+
+def test_rotation_lowers_the_draft_mode_error_on_outlier_channels():
+    """The purpose of the rotation: with one channel in a hundred 20 times larger, the
+    4-bit activation grid of its group is 20 times coarser for the other 127 channels;
+    after the rotation the energy is spread.  Weights are the same random codes in both
+    runs (they stand for a checkpoint quantised in the respective basis)."""
+    codes, scales, x = synth.generic_case(54, 16, 64, 1024)
+    w = orc.dequant_weights(codes, scales) if hasattr(orc, "dequant_weights") else \
+        codes.astype(np.float64) * np.repeat(scales.astype(np.float64), 128, axis=1)
+
+    def rel_err(xin):
+        qa, sa = orc.quant_act(xin)
+        xq = qa.astype(np.float64) * np.repeat(sa.astype(np.float64), 128, axis=1)
+        exact = xin.astype(np.float64) @ w.T
+        return np.linalg.norm(xq @ w.T - exact) / np.linalg.norm(exact)
+
+    plain, rotated = rel_err(x), rel_err(rot.hadamard128_f16(x))
+    assert rotated < 0.6 * plain, (plain, rotated)
