@@ -133,6 +133,24 @@ int qspec_silu_mul_quant(const void* gate_up_f16, int M, int I, int group,
                          uint8_t* qa, float* sa, void* h_f16, void* stream);
 
 /*
+ * Outlier-spreading rotation fused with the quantiser (paper Sec. 4.1 builds on
+ * existing 4-bit quantisers, a rotation-based one among them; the paper gives no
+ * detail, the block-diagonal form is this library's): every group of 128 input
+ * features is multiplied by the Sylvester Hadamard matrix H_128 (natural order,
+ * H[i][j] = (-1)^popcount(i & j)) and by 2^-3, then quantised as qspec_quant_act does:
+ *   h[m, 128 j .. 128 j + 127] = fp16( x[m, 128 j .. 128 j + 127] H_128 / 8 )
+ * The transform runs in binary32 as the fast transform with stages h = 1, 2, ..., 64
+ * (stage h replaces v[i], v[i+h] by v[i] + v[i+h], v[i] - v[i+h]).  A layer that is
+ * fed these activations holds its weights in the rotated basis (w_g H_128 / 16 per
+ * group, prepared offline before qspec_pack_weights), so that h w'^T = x w^T; the
+ * verify mode takes h_f16 as its input.
+ *   x_f16 fp16 [M,K];  qa, sa out, as qspec_quant_act writes them for h;
+ *   h_f16 out, fp16 [M,K], or NULL.
+ */
+int qspec_hadamard_quant(const void* x_f16, int M, int K, int group,
+                         uint8_t* qa, float* sa, void* h_f16, void* stream);
+
+/*
  * Draft-mode product (paper Sec. 1: W4A4 runs on the low-precision matrix
  * units without dequantising to a higher precision):
  *   P[m,n,j] = sum_{k in group j} qa[m,k] * qw[n,k]             (int32, exact)

@@ -20,7 +20,7 @@ EXPORTS = (
     "qspec_pack_weights", "qspec_unpack_weights", "qspec_quant_act", "qspec_gemm_w4a4",
     "qspec_gemm_w4a16", "qspec_gemm_w4a4_partials", "qspec_describe_kernel",
     "qspec_accept_workspace_bytes", "qspec_greedy_accept", "qspec_kv_overwrite",
-    "qspec_rmsnorm_quant", "qspec_silu_mul_quant",
+    "qspec_rmsnorm_quant", "qspec_silu_mul_quant", "qspec_hadamard_quant",
 )
 
 
@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.qspec_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, ci, ci, ci, vp, vp, vp, vp]
     L.qspec_silu_mul_quant.restype = ci
     L.qspec_silu_mul_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+    L.qspec_hadamard_quant.restype = ci
+    L.qspec_hadamard_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -209,6 +211,19 @@ def silu_mul_quant(gate_up: torch.Tensor, qa: torch.Tensor = None, sa: torch.Ten
                                       _dev(qa, torch.uint8, "qa"), _dev(sa, torch.float32, "sa"),
                                       None if h is None else _dev(h, torch.float16, "h"), _stream()),
            "qspec_silu_mul_quant")
+    return qa, sa, h
+
+
+def hadamard_quant(x: torch.Tensor, qa: torch.Tensor = None, sa: torch.Tensor = None,
+                   h: torch.Tensor = None, want_h: bool = False, group: int = GROUP):
+    """Every group of 128 features times H_128 / 8, then the activation quantiser: x fp16 [M,K] ->
+    (qa uint8 [M,K/2], sa fp32 [M,K/128], h fp16 [M,K] or None)."""
+    M, K = x.shape
+    qa, sa, h = _quant_outputs(M, K, group, x.device, qa, sa, h, want_h)
+    _check(lib().qspec_hadamard_quant(_dev(x, torch.float16, "x"), M, K, group,
+                                      _dev(qa, torch.uint8, "qa"), _dev(sa, torch.float32, "sa"),
+                                      None if h is None else _dev(h, torch.float16, "h"), _stream()),
+           "qspec_hadamard_quant")
     return qa, sa, h
 
 

@@ -165,4 +165,74 @@ __global__ __launch_bounds__(256) void silu_mul_quant_kernel(const uint4* __rest
   quantise_unit(v, live, idx, qa_words, sa);
 }
 
+// ---- outlier-spreading rotation in front of the quantiser: every group of 128
+// features times H_128 / 8 (Sylvester Hadamard matrix, natural order), the
+// rotation-based quantisers' answer to single large channels (paper Sec. 4.1 names
+// such a quantiser among those it builds on; the block-diagonal form, which keeps the
+// transform inside one quantisation group and one row of 16 lanes, is this build's).
+// The weights are stored in the rotated basis (w_g H_128 / 16, offline), so the
+// product is unchanged.  Arithmetic: the fast transform in binary32, stage h = 1, 2,
+// ..., 64 replacing (v[j], v[j+h]) by (v[j] + v[j+h], v[j] - v[j+h]); scaling by 2^-3
+// (exact); one rounding to fp16.  A thread's 8 values cover stages 1, 2, 4; stages 8
+// to 64 pair lane l with lane l ^ 1, 2, 4, 8 of its row (DPP moves).
+template <int CTRL>
+__device__ inline float dpp_f32(float v) {
+  return __builtin_bit_cast(float, dpp_i32<CTRL>(__builtin_bit_cast(int, v)));
+}
+
+// One stage across lanes: `other` is the partner lane's value, `upper` says whether
+// this lane holds the v[j+h] side of its pairs.
+__device__ inline float butterfly(float mine, float other, bool upper) {
+  return upper ? other - mine : mine + other;
+}
+
+__global__ __launch_bounds__(256) void hadamard_quant_kernel(const uint4* __restrict__ x,
+                                                             uint32_t* __restrict__ qa_words,
+                                                             float* __restrict__ sa, uint4* __restrict__ h_out,
+                                                             size_t n_words) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool live = idx < n_words;
+  uint4 raw = {0u, 0u, 0u, 0u};
+  if (live) raw = x[idx];
+  float v[8];
+  {
+    const v8h h = __builtin_bit_cast(v8h, raw);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)h[e];
+  }
+  // stages 1, 2, 4 inside the thread
+#pragma unroll
+  for (int h = 1; h < 8; h <<= 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if ((e & h) == 0) {
+        const float a = v[e], b = v[e + h];
+        v[e] = a + b;
+        v[e + h] = a - b;
+      }
+    }
+  }
+  // stages 8, 16, 32, 64 across the 16 lanes of the row
+  const int l = threadIdx.x & 15;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float t = v[e];
+    t = butterfly(t, dpp_f32<0xB1>(t), (l & 1) != 0);                  // lane ^ 1
+    t = butterfly(t, dpp_f32<0x4E>(t), (l & 2) != 0);                  // lane ^ 2
+    // lane ^ 4: four lanes up for the lower side (a rotation by 12), four down for the upper
+    const float up4 = dpp_f32<0x12C>(t), down4 = dpp_f32<0x124>(t);
+    t = butterfly(t, (l & 4) ? down4 : up4, (l & 4) != 0);
+    t = butterfly(t, dpp_f32<0x128>(t), (l & 8) != 0);                 // lane ^ 8: a rotation by 8
+    v[e] = t;
+  }
+  v8h hh;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    hh[e] = (_Float16)(v[e] * 0.125f);                                 // exact scaling: one rounding either way
+    v[e] = (float)hh[e];
+  }
+  if (h_out != nullptr && live) h_out[idx] = __builtin_bit_cast(uint4, hh);
+  quantise_unit(v, live, idx, qa_words, sa);
+}
+
 }  // namespace qspec

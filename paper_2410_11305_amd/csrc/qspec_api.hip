@@ -528,6 +528,19 @@ int qspec_silu_mul_quant(const void* gate_up_f16, int M, int I, int group,
   return launch_status();
 }
 
+int qspec_hadamard_quant(const void* x_f16, int M, int K, int group,
+                         uint8_t* qa, float* sa, void* h_f16, void* stream) {
+  if (!x_f16 || !qa || !sa) return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, kTileRows, K, group)) return st;
+  if (misaligned(x_f16) || misaligned(qa) || misaligned(sa) || misaligned(h_f16)) return QSPEC_ERR_ALIGN;
+  if (int st = check_device()) return st;
+  const size_t n_words = (size_t)M * K / 8;
+  hipLaunchKernelGGL(hadamard_quant_kernel, dim3(blocks_for(n_words, 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(x_f16),
+                     reinterpret_cast<uint32_t*>(qa), sa, static_cast<uint4*>(h_f16), n_words);
+  return launch_status();
+}
+
 int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int M, int N, int K, int group,
                     void* y_f16, void* workspace, size_t workspace_bytes, void* stream) {
   if (!packed || !qa || !sa || !y_f16) return QSPEC_ERR_NULL;

@@ -8,6 +8,7 @@ import pytest
 from oracle import device_layout as lay
 from oracle import producers_oracle as prod
 from oracle import qspec_oracle as orc
+from oracle import rotation_oracle as rot
 from paper_2410_11305_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -120,6 +121,68 @@ def test_producers_on_benchmark_shapes_feed_the_draft_gemm(env, config):
     assert torch.equal(y1, y2)
 
 
+def run_hadamard(env, x, want_h=True):
+    torch, B = env
+    qa, sa, h = B.hadamard_quant(dev(torch, x), want_h=want_h)
+    check_against(torch, qa, sa, h, rot.hadamard128_f16(x))
+    return qa, sa, h
+
+
+@pytest.mark.parametrize("M,K", [(1, 128), (3, 256), (5, 1024), (8, 4096), (32, 11008), (128, 28672), (515, 384)])
+def test_hadamard_quant_bit_exact(env, M, K):
+    _, _, x = synth.generic_case(500 + M + K, M, 16, K)
+    run_hadamard(env, x)
+    run_hadamard(env, x, want_h=False)
+
+
+def test_hadamard_quant_special_rows(env):
+    K = 256
+    rng = np.random.default_rng(9)
+    x = np.zeros((8, K), dtype=np.float16)
+    x[1, 5] = 8.0                                          # one-hot: a row of the matrix, +-1
+    x[2] = 1.0                                             # constant: only entry 0 of each group survives (16)
+    x[3] = rng.integers(-40, 41, K)                        # integers: every sum exact
+    x[4] = rng.standard_normal(K) * 6e-5                   # subnormal neighbourhood
+    x[5] = rng.standard_normal(K) * 400.0                  # sums near the top of the fp16 range / 8
+    x[6, 128:] = rng.standard_normal(128)                  # first group all zero
+    x[7] = rng.standard_normal(K)
+    x[7, 200] = 90.0                                       # one dominant channel
+    _, _, h = run_hadamard(env, x)
+    h = h.cpu().numpy()
+    assert sorted(set(np.abs(h[1, :128]).tolist())) == [1.0] and not h[1, 128:].any()
+    assert h[2, 0] == 16 and h[2, 128] == 16 and np.count_nonzero(h[2]) == 2
+
+
+def test_rotated_activations_give_the_same_product_with_rotated_weights(env):
+    """x' = x H / 8 and w' = w H / 16 per group: x' w'^T = x w^T.  Checked end to end on the
+    device in verify mode with weights whose rotated form is exactly representable (every
+    group of a weight row is a signed row of H, so w H / 16 is 8 times a unit vector)."""
+    torch, B = env
+    from scipy.linalg import hadamard
+    H = hadamard(128).astype(np.int64)
+    rng = np.random.default_rng(10)
+    N, K, M = 64, 512, 24
+    G = K // 128
+    pick = rng.integers(0, 128, (N, G))
+    sign = rng.choice([-1, 1], (N, G))
+    codes_plain = (H[pick] * sign[:, :, None]).reshape(N, K).astype(np.int8)          # entries +-1
+    codes_rot = np.zeros((N, G, 128), dtype=np.int8)
+    np.put_along_axis(codes_rot, pick[:, :, None], (8 * sign)[:, :, None].astype(np.int8), axis=2)
+    codes_rot = codes_rot.reshape(N, K)        # (w_g H / 16): 128 / 16 = 8 at the picked position... as a code of scale 1
+    scales = np.ones((N, G), dtype=np.float16)
+    # the code range stops at 7: carry the factor in the scale instead (code 4, scale 2)
+    codes_rot = (codes_rot // 2).astype(np.int8)
+    scales_rot = np.full((N, G), 2.0, dtype=np.float16)
+    x = rng.integers(-20, 21, (M, K)).astype(np.float16)
+    _, _, h = B.hadamard_quant(dev(torch, x), want_h=True)
+    y_plain = B.gemm_w4a16(B.pack_weights(dev(torch, codes_plain), dev(torch, scales)), dev(torch, x), N)
+    y_rot = B.gemm_w4a16(B.pack_weights(dev(torch, codes_rot), dev(torch, scales_rot)), h, N)
+    torch.cuda.synchronize()
+    ref = x.astype(np.float64) @ codes_plain.astype(np.float64).T
+    assert np.array_equal(y_plain.cpu().numpy().astype(np.float64), ref.astype(np.float16).astype(np.float64))
+    assert torch.equal(y_plain, y_rot)
+
+
 def test_bad_arguments_are_refused(env):
     torch, B = env
     x = torch.zeros((2, 256), dtype=torch.float16, device="cuda")
@@ -132,4 +195,6 @@ def test_bad_arguments_are_refused(env):
         B.rmsnorm_quant(x[:, :192].contiguous(), w[:192].contiguous(), 1e-5)      # K not a multiple of 128
     with pytest.raises(B.QSpecError):
         B.silu_mul_quant(torch.zeros((2, 2 * 192), dtype=torch.float16, device="cuda"))
+    with pytest.raises(B.QSpecError):
+        B.hadamard_quant(torch.zeros((2, 192), dtype=torch.float16, device="cuda"))
     torch.cuda.synchronize()
