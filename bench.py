@@ -363,6 +363,10 @@ def main() -> int:
         "silu_mul_quant_us": round(per_call(lambda: B.silu_mul_quant(pgu, pq_i[0], pq_i[1])), 3),
         "quant_act_alone_intermediate_us": round(per_call(lambda: B.quant_act(pi, pq_i[0], pq_i[1])), 3),
         "torch_silu_mul_then_quant_act_us": round(per_call(lambda: B.quant_act(torch_silu(), pq_i[0], pq_i[1])), 3),
+        # with the per-group Hadamard rotation in front of the quantiser
+        "hadamard_quant_hidden_us": round(per_call(lambda: B.hadamard_quant(ph, pq_h[0], pq_h[1])), 3),
+        "rmsnorm_rotate_quant_us": round(per_call(lambda: B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1], rotate=True)), 3),
+        "silu_mul_rotate_quant_us": round(per_call(lambda: B.silu_mul_quant(pgu, pq_i[0], pq_i[1], rotate=True)), 3),
     }
     fused_producers["silu_mul_quant_GBps"] = round((Md * Ii * 4 + Md * Ii // 2 + Md * (Ii // 128) * 4)
                                                    / fused_producers["silu_mul_quant_us"] / 1e3, 1)

@@ -124,13 +124,15 @@ int qspec_quant_act(const void* x_f16, int M, int K, int group,
  *               eps = 0 gives zeros);
  *   gate_up_f16 fp16 [M,2I], the gate in the first I columns; I a positive multiple of 128;
  *   qa, sa      out, as qspec_quant_act writes them for h ([M,K] resp. [M,I]);
+ *   rotate      0, or 1: h is replaced by its rotation (qspec_hadamard_quant below, applied
+ *               to the fp16 tensor h) before it is stored and quantised;
  *   h_f16       out, fp16 [M,K] resp. [M,I], or NULL when the tensor itself is not
  *               needed (the draft pass needs only the codes).
  */
 int qspec_rmsnorm_quant(const void* x_f16, const void* weight_f16, float eps, int M, int K, int group,
-                        uint8_t* qa, float* sa, void* h_f16, void* stream);
+                        int rotate, uint8_t* qa, float* sa, void* h_f16, void* stream);
 int qspec_silu_mul_quant(const void* gate_up_f16, int M, int I, int group,
-                         uint8_t* qa, float* sa, void* h_f16, void* stream);
+                         int rotate, uint8_t* qa, float* sa, void* h_f16, void* stream);
 
 /*
  * Outlier-spreading rotation fused with the quantiser (paper Sec. 4.1 builds on

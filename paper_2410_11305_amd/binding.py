@@ -73,9 +73,9 @@ def lib() -> ctypes.CDLL:
     L.qspec_kv_overwrite.restype = ci
     L.qspec_kv_overwrite.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
     L.qspec_rmsnorm_quant.restype = ci
-    L.qspec_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, ci, ci, ci, vp, vp, vp, vp]
+    L.qspec_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, ci, ci, ci, ci, vp, vp, vp, vp]
     L.qspec_silu_mul_quant.restype = ci
-    L.qspec_silu_mul_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+    L.qspec_silu_mul_quant.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
     L.qspec_hadamard_quant.restype = ci
     L.qspec_hadamard_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     _lib = L
@@ -188,13 +188,14 @@ def _quant_outputs(M, K, group, device, qa, sa, h, want_h):
 
 
 def rmsnorm_quant(x: torch.Tensor, weight: torch.Tensor, eps: float, qa: torch.Tensor = None,
-                  sa: torch.Tensor = None, h: torch.Tensor = None, want_h: bool = False, group: int = GROUP):
-    """RMSNorm fused with the activation quantiser: x fp16 [M,K], weight fp16 [K] ->
-    (qa uint8 [M,K/2], sa fp32 [M,K/128], h fp16 [M,K] or None)."""
+                  sa: torch.Tensor = None, h: torch.Tensor = None, want_h: bool = False, rotate: bool = False,
+                  group: int = GROUP):
+    """RMSNorm (then, if `rotate`, the per-group Hadamard rotation) fused with the activation
+    quantiser: x fp16 [M,K], weight fp16 [K] -> (qa uint8 [M,K/2], sa fp32 [M,K/128], h fp16 [M,K] or None)."""
     M, K = x.shape
     qa, sa, h = _quant_outputs(M, K, group, x.device, qa, sa, h, want_h)
     _check(lib().qspec_rmsnorm_quant(_dev(x, torch.float16, "x"), _dev(weight, torch.float16, "weight"),
-                                     float(eps), M, K, group, _dev(qa, torch.uint8, "qa"),
+                                     float(eps), M, K, group, int(bool(rotate)), _dev(qa, torch.uint8, "qa"),
                                      _dev(sa, torch.float32, "sa"),
                                      None if h is None else _dev(h, torch.float16, "h"), _stream()),
            "qspec_rmsnorm_quant")
@@ -202,12 +203,12 @@ def rmsnorm_quant(x: torch.Tensor, weight: torch.Tensor, eps: float, qa: torch.T
 
 
 def silu_mul_quant(gate_up: torch.Tensor, qa: torch.Tensor = None, sa: torch.Tensor = None,
-                   h: torch.Tensor = None, want_h: bool = False, group: int = GROUP):
-    """SiLU(gate) * up fused with the activation quantiser: gate_up fp16 [M,2I] (gate first) ->
-    (qa uint8 [M,I/2], sa fp32 [M,I/128], h fp16 [M,I] or None)."""
+                   h: torch.Tensor = None, want_h: bool = False, rotate: bool = False, group: int = GROUP):
+    """SiLU(gate) * up (then, if `rotate`, the per-group Hadamard rotation) fused with the activation
+    quantiser: gate_up fp16 [M,2I] (gate first) -> (qa uint8 [M,I/2], sa fp32 [M,I/128], h fp16 [M,I] or None)."""
     M, I = gate_up.shape[0], gate_up.shape[1] // 2
     qa, sa, h = _quant_outputs(M, I, group, gate_up.device, qa, sa, h, want_h)
-    _check(lib().qspec_silu_mul_quant(_dev(gate_up, torch.float16, "gate_up"), M, I, group,
+    _check(lib().qspec_silu_mul_quant(_dev(gate_up, torch.float16, "gate_up"), M, I, group, int(bool(rotate)),
                                       _dev(qa, torch.uint8, "qa"), _dev(sa, torch.float32, "sa"),
                                       None if h is None else _dev(h, torch.float16, "h"), _stream()),
            "qspec_silu_mul_quant")

@@ -57,6 +57,77 @@ __device__ inline double wave_sum_f64(double v) {
   return (lane_value_f64(v, 0) + lane_value_f64(v, 16)) + (lane_value_f64(v, 32) + lane_value_f64(v, 48));
 }
 
+// ---- outlier-spreading rotation in front of the quantiser: every group of 128
+// features times H_128 / 8 (Sylvester Hadamard matrix, natural order), the
+// rotation-based quantisers' answer to single large channels (paper Sec. 4.1 names
+// such a quantiser among those it builds on; the block-diagonal form, which keeps the
+// transform inside one quantisation group and one row of 16 lanes, is this build's).
+// The weights are stored in the rotated basis (w_g H_128 / 16, offline), so the
+// product is unchanged.  Arithmetic: the fast transform in binary32, stage h = 1, 2,
+// ..., 64 replacing (v[j], v[j+h]) by (v[j] + v[j+h], v[j] - v[j+h]); scaling by 2^-3
+// (exact); one rounding to fp16.  A thread's 8 values cover stages 1, 2, 4; stages 8
+// to 64 pair lane l with lane l ^ 1, 2, 4, 8 of its row (DPP moves).
+template <int CTRL>
+__device__ inline float dpp_f32(float v) {
+  return __builtin_bit_cast(float, dpp_i32<CTRL>(__builtin_bit_cast(int, v)));
+}
+
+// One stage across lanes: `other` is the partner lane's value, `upper` says whether
+// this lane holds the v[j+h] side of its pairs.
+__device__ inline float butterfly(float mine, float other, bool upper) {
+  return upper ? other - mine : mine + other;
+}
+
+// The transform of one group held by a row of 16 lanes, 8 consecutive values per lane
+// (l = lane within the row); every lane of the row must be active.
+__device__ inline void hadamard_row16(float (&v)[8], int l) {
+  // stages 1, 2, 4 inside the thread
+#pragma unroll
+  for (int h = 1; h < 8; h <<= 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if ((e & h) == 0) {
+        const float a = v[e], b = v[e + h];
+        v[e] = a + b;
+        v[e + h] = a - b;
+      }
+    }
+  }
+  // stages 8, 16, 32, 64 across the 16 lanes of the row
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float t = v[e];
+    t = butterfly(t, dpp_f32<0xB1>(t), (l & 1) != 0);                  // lane ^ 1
+    t = butterfly(t, dpp_f32<0x4E>(t), (l & 2) != 0);                  // lane ^ 2
+    // lane ^ 4: four lanes up for the lower side (a rotation by 12), four down for the upper
+    const float up4 = dpp_f32<0x12C>(t), down4 = dpp_f32<0x124>(t);
+    t = butterfly(t, (l & 4) ? down4 : up4, (l & 4) != 0);
+    t = butterfly(t, dpp_f32<0x128>(t), (l & 8) != 0);                 // lane ^ 8: a rotation by 8
+    v[e] = t;
+  }
+}
+
+// v: 8 fp16 values widened to binary32.  Rotates (if asked), rounds to fp16, stores the
+// fp16 tensor (if asked) and quantises.  Every lane of the wavefront calls it.
+__device__ inline void finish_unit(float (&v)[8], bool rotate, bool live, size_t idx,
+                                   uint32_t* __restrict__ qa_words, float* __restrict__ sa,
+                                   uint4* __restrict__ h_out) {
+  v8h hh;
+  if (rotate) {
+    hadamard_row16(v, threadIdx.x & 15);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      hh[e] = (_Float16)(v[e] * 0.125f);                               // exact scaling: one rounding either way
+      v[e] = (float)hh[e];
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) hh[e] = (_Float16)v[e];                // v holds fp16 values: exact
+  }
+  if (h_out != nullptr && live) h_out[idx] = __builtin_bit_cast(uint4, hh);
+  quantise_unit(v, live, idx, qa_words, sa);
+}
+
 // 1/sqrt(v) in binary64 to within a few units in the last place, v > 0 and normal: the
 // hardware estimate and three Newton steps (each squares the relative error), instead of
 // the correctly rounded square root and division, whose long dependent chains would sit
@@ -81,7 +152,7 @@ __global__ __launch_bounds__(kRowMaxThreads) void rmsnorm_quant_kernel(const uin
                                                                        int K, double inv_K,
                                                                        uint32_t* __restrict__ qa_words,
                                                                        float* __restrict__ sa,
-                                                                       uint4* __restrict__ h_out) {
+                                                                       uint4* __restrict__ h_out, int rotate) {
   const int tid = threadIdx.x, T = blockDim.x;
   const int kw = K / 8;                                    // 16-byte pieces per row
   const size_t row0 = (size_t)blockIdx.x * kw;
@@ -123,16 +194,13 @@ __global__ __launch_bounds__(kRowMaxThreads) void rmsnorm_quant_kernel(const uin
     const uint4 wraw = NCH > 0 ? wkeep[c] : (live ? w[piece] : zero);
     const v8h xh = __builtin_bit_cast(v8h, raw);
     const v8h wh = __builtin_bit_cast(v8h, wraw);
-    v8h hh;
     float v8[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float t = (float)xh[e] * (float)wh[e];         // exact
-      hh[e] = (_Float16)rounded_f32(t * r);
-      v8[e] = (float)hh[e];
+      v8[e] = (float)(_Float16)rounded_f32(t * r);
     }
-    if (h_out != nullptr && live) h_out[row0 + piece] = __builtin_bit_cast(uint4, hh);
-    quantise_unit(v8, live, row0 + piece, qa_words, sa);
+    finish_unit(v8, rotate != 0, live, row0 + piece, qa_words, sa, h_out);
   }
 }
 
@@ -141,7 +209,7 @@ __global__ __launch_bounds__(kRowMaxThreads) void rmsnorm_quant_kernel(const uin
 __global__ __launch_bounds__(256) void silu_mul_quant_kernel(const uint4* __restrict__ gate_up, int I8,
                                                              uint32_t* __restrict__ qa_words,
                                                              float* __restrict__ sa, uint4* __restrict__ h_out,
-                                                             size_t n_words) {
+                                                             size_t n_words, int rotate) {
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const bool live = idx < n_words;
   uint4 graw = {0u, 0u, 0u, 0u}, uraw = {0u, 0u, 0u, 0u};
@@ -152,38 +220,14 @@ __global__ __launch_bounds__(256) void silu_mul_quant_kernel(const uint4* __rest
   }
   const v8h gh = __builtin_bit_cast(v8h, graw);
   const v8h uh = __builtin_bit_cast(v8h, uraw);
-  v8h hh;
   float v[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const double g = (double)(float)gh[e];
     const float s = (float)(g / (1.0 + exp(-g)));
-    hh[e] = (_Float16)rounded_f32(s * (float)uh[e]);
-    v[e] = (float)hh[e];
+    v[e] = (float)(_Float16)rounded_f32(s * (float)uh[e]);
   }
-  if (h_out != nullptr && live) h_out[idx] = __builtin_bit_cast(uint4, hh);
-  quantise_unit(v, live, idx, qa_words, sa);
-}
-
-// ---- outlier-spreading rotation in front of the quantiser: every group of 128
-// features times H_128 / 8 (Sylvester Hadamard matrix, natural order), the
-// rotation-based quantisers' answer to single large channels (paper Sec. 4.1 names
-// such a quantiser among those it builds on; the block-diagonal form, which keeps the
-// transform inside one quantisation group and one row of 16 lanes, is this build's).
-// The weights are stored in the rotated basis (w_g H_128 / 16, offline), so the
-// product is unchanged.  Arithmetic: the fast transform in binary32, stage h = 1, 2,
-// ..., 64 replacing (v[j], v[j+h]) by (v[j] + v[j+h], v[j] - v[j+h]); scaling by 2^-3
-// (exact); one rounding to fp16.  A thread's 8 values cover stages 1, 2, 4; stages 8
-// to 64 pair lane l with lane l ^ 1, 2, 4, 8 of its row (DPP moves).
-template <int CTRL>
-__device__ inline float dpp_f32(float v) {
-  return __builtin_bit_cast(float, dpp_i32<CTRL>(__builtin_bit_cast(int, v)));
-}
-
-// One stage across lanes: `other` is the partner lane's value, `upper` says whether
-// this lane holds the v[j+h] side of its pairs.
-__device__ inline float butterfly(float mine, float other, bool upper) {
-  return upper ? other - mine : mine + other;
+  finish_unit(v, rotate != 0, live, idx, qa_words, sa, h_out);
 }
 
 __global__ __launch_bounds__(256) void hadamard_quant_kernel(const uint4* __restrict__ x,
@@ -200,39 +244,7 @@ __global__ __launch_bounds__(256) void hadamard_quant_kernel(const uint4* __rest
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (float)h[e];
   }
-  // stages 1, 2, 4 inside the thread
-#pragma unroll
-  for (int h = 1; h < 8; h <<= 1) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if ((e & h) == 0) {
-        const float a = v[e], b = v[e + h];
-        v[e] = a + b;
-        v[e + h] = a - b;
-      }
-    }
-  }
-  // stages 8, 16, 32, 64 across the 16 lanes of the row
-  const int l = threadIdx.x & 15;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    float t = v[e];
-    t = butterfly(t, dpp_f32<0xB1>(t), (l & 1) != 0);                  // lane ^ 1
-    t = butterfly(t, dpp_f32<0x4E>(t), (l & 2) != 0);                  // lane ^ 2
-    // lane ^ 4: four lanes up for the lower side (a rotation by 12), four down for the upper
-    const float up4 = dpp_f32<0x12C>(t), down4 = dpp_f32<0x124>(t);
-    t = butterfly(t, (l & 4) ? down4 : up4, (l & 4) != 0);
-    t = butterfly(t, dpp_f32<0x128>(t), (l & 8) != 0);                 // lane ^ 8: a rotation by 8
-    v[e] = t;
-  }
-  v8h hh;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    hh[e] = (_Float16)(v[e] * 0.125f);                                 // exact scaling: one rounding either way
-    v[e] = (float)hh[e];
-  }
-  if (h_out != nullptr && live) h_out[idx] = __builtin_bit_cast(uint4, hh);
-  quantise_unit(v, live, idx, qa_words, sa);
+  finish_unit(v, true, live, idx, qa_words, sa, h_out);
 }
 
 }  // namespace qspec

@@ -490,10 +490,10 @@ int qspec_quant_act(const void* x_f16, int M, int K, int group, uint8_t* qa, flo
 }
 
 int qspec_rmsnorm_quant(const void* x_f16, const void* weight_f16, float eps, int M, int K, int group,
-                        uint8_t* qa, float* sa, void* h_f16, void* stream) {
+                        int rotate, uint8_t* qa, float* sa, void* h_f16, void* stream) {
   if (!x_f16 || !weight_f16 || !qa || !sa) return QSPEC_ERR_NULL;
   if (int st = check_shape(M, kTileRows, K, group)) return st;
-  if (!(eps >= 0.0f) || !(eps <= 3.0e38f)) return QSPEC_ERR_SHAPE;
+  if (!(eps >= 0.0f) || !(eps <= 3.0e38f) || (rotate != 0 && rotate != 1)) return QSPEC_ERR_SHAPE;
   if (misaligned(x_f16) || misaligned(weight_f16) || misaligned(qa) || misaligned(sa) || misaligned(h_f16))
     return QSPEC_ERR_ALIGN;
   if (int st = check_device()) return st;
@@ -508,23 +508,24 @@ int qspec_rmsnorm_quant(const void* x_f16, const void* weight_f16, float eps, in
   const int chunks = (kw + T - 1) / T;
   const double inv_K = 1.0 / (double)K;
   const dim3 grid(M), block(T);
-  if (chunks <= 1) hipLaunchKernelGGL(rmsnorm_quant_kernel<1>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h);
-  else if (chunks <= 2) hipLaunchKernelGGL(rmsnorm_quant_kernel<2>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h);
-  else if (chunks <= 4) hipLaunchKernelGGL(rmsnorm_quant_kernel<4>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h);
-  else hipLaunchKernelGGL(rmsnorm_quant_kernel<0>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h);
+  if (chunks <= 1) hipLaunchKernelGGL(rmsnorm_quant_kernel<1>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h, rotate);
+  else if (chunks <= 2) hipLaunchKernelGGL(rmsnorm_quant_kernel<2>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h, rotate);
+  else if (chunks <= 4) hipLaunchKernelGGL(rmsnorm_quant_kernel<4>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h, rotate);
+  else hipLaunchKernelGGL(rmsnorm_quant_kernel<0>, grid, block, 0, s, x, w, eps, K, inv_K, words, sa, h, rotate);
   return launch_status();
 }
 
 int qspec_silu_mul_quant(const void* gate_up_f16, int M, int I, int group,
-                         uint8_t* qa, float* sa, void* h_f16, void* stream) {
+                         int rotate, uint8_t* qa, float* sa, void* h_f16, void* stream) {
   if (!gate_up_f16 || !qa || !sa) return QSPEC_ERR_NULL;
   if (int st = check_shape(M, kTileRows, I, group)) return st;
+  if (rotate != 0 && rotate != 1) return QSPEC_ERR_SHAPE;
   if (misaligned(gate_up_f16) || misaligned(qa) || misaligned(sa) || misaligned(h_f16)) return QSPEC_ERR_ALIGN;
   if (int st = check_device()) return st;
   const size_t n_words = (size_t)M * I / 8;
   hipLaunchKernelGGL(silu_mul_quant_kernel, dim3(blocks_for(n_words, 256)), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint4*>(gate_up_f16), I / 8,
-                     reinterpret_cast<uint32_t*>(qa), sa, static_cast<uint4*>(h_f16), n_words);
+                     reinterpret_cast<uint32_t*>(qa), sa, static_cast<uint4*>(h_f16), n_words, rotate);
   return launch_status();
 }
 

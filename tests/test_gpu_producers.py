@@ -37,17 +37,19 @@ def check_against(torch, qa, sa, h, h_ref):
     assert np.array_equal(qa.cpu().numpy(), lay.act_bytes(q_ref))
 
 
-def run_rmsnorm(env, x, w, eps, want_h=True):
+def run_rmsnorm(env, x, w, eps, want_h=True, rotate=False):
     torch, B = env
-    qa, sa, h = B.rmsnorm_quant(dev(torch, x), dev(torch, w), eps, want_h=want_h)
-    check_against(torch, qa, sa, h, prod.rmsnorm_f16(x, w, eps))
+    qa, sa, h = B.rmsnorm_quant(dev(torch, x), dev(torch, w), eps, want_h=want_h, rotate=rotate)
+    h_ref = prod.rmsnorm_f16(x, w, eps)
+    check_against(torch, qa, sa, h, rot.hadamard128_f16(h_ref) if rotate else h_ref)
     return qa, sa
 
 
-def run_silu(env, gu, want_h=True):
+def run_silu(env, gu, want_h=True, rotate=False):
     torch, B = env
-    qa, sa, h = B.silu_mul_quant(dev(torch, gu), want_h=want_h)
-    check_against(torch, qa, sa, h, prod.silu_mul_f16(gu))
+    qa, sa, h = B.silu_mul_quant(dev(torch, gu), want_h=want_h, rotate=rotate)
+    h_ref = prod.silu_mul_f16(gu)
+    check_against(torch, qa, sa, h, rot.hadamard128_f16(h_ref) if rotate else h_ref)
     return qa, sa
 
 
@@ -60,6 +62,7 @@ def test_rmsnorm_quant_bit_exact(env, M, K):
     x, w, _ = synth.producer_case(300 + M + K, M, K, 128)
     run_rmsnorm(env, x, w, synth.RMS_EPS)
     run_rmsnorm(env, x, w, synth.RMS_EPS, want_h=False)
+    run_rmsnorm(env, x, w, synth.RMS_EPS, rotate=True)
 
 
 def test_rmsnorm_quant_special_rows(env):
@@ -83,6 +86,7 @@ def test_silu_mul_quant_bit_exact(env, M, I):
     _, _, gu = synth.producer_case(400 + M + I, M, 128, I)
     run_silu(env, gu)
     run_silu(env, gu, want_h=False)
+    run_silu(env, gu, rotate=True)
 
 
 def test_silu_mul_quant_whole_gate_range(env):
