@@ -761,3 +761,113 @@ def test_rotation_lowers_the_draft_mode_error_on_outlier_channels():
 
     plain, rotated = rel_err(x), rel_err(rot.hadamard128_f16(x))
     assert rotated < 0.6 * plain, (plain, rotated)
+
+
+# ---------------------------------------------------------------- reordering quantiser (outlier groups at ~8 bits)
+from oracle import reorder_oracle as reo
+
+
+def test_reorder_quant_hand_worked_group():
+    rows = {}
+    for line in open(os.path.join(GOLDEN, "reorder_quant_worked_group.txt")):
+        if line.startswith("#") or ":" not in line:
+            continue
+        key, vals = line.split(":")
+        rows[key.strip()] = [float(v) for v in vals.split()]
+    x = np.zeros((1, 128), dtype=np.float16)
+    x[0, :8] = rows["x"]
+    codes, scales = reo.reorder_quant(x, np.arange(128), 1)
+    assert codes.shape == (1, 256) and scales.shape == (1, 2)
+    assert codes[0, :8].tolist() == rows["hi"] and codes[0, 128:136].tolist() == rows["lo"]
+    assert not codes[0, 8:128].any() and not codes[0, 136:].any()
+    assert scales[0].tolist() == [rows["scale_hi"][0], rows["scale_lo"][0]]
+
+
+def test_reorder_quant_digits_cover_the_whole_range():
+    for q8 in range(-119, 120):
+        lo = ((q8 + 8) % 16) - 8
+        hi = (q8 - lo) // 16
+        assert -8 <= lo <= 7 and -7 <= hi <= 7 and 16 * hi + lo == q8
+    # through the oracle: a group holding every level once (a = 119, s = 1)
+    x = np.zeros((1, 256), dtype=np.float16)
+    x[0, :239] = np.arange(-119, 120)
+    perm = np.concatenate([np.arange(128, 256), np.arange(0, 128)])      # put group 0 last, as the outlier group
+    codes, scales = reo.reorder_quant(x, perm, 1)
+    hi, lo = codes[0, 128:256].astype(np.int64), codes[0, 256:384].astype(np.int64)
+    assert np.array_equal(16 * hi + lo, np.arange(-119, 9))              # the gathered group 0 of x
+    assert scales[0, 1] == 16.0 and scales[0, 2] == 1.0
+
+
+def test_reorder_quant_vs_exact_rationals():
+    rng = np.random.default_rng(61)
+    K, Go = 384, 2
+    x = (rng.standard_normal((3, K)) * 2.0).astype(np.float16)
+    x[:, [5, 130, 300]] *= 20
+    perm = rng.permutation(K)
+    codes, scales = reo.reorder_quant(x, perm, Go)
+    G = K // 128
+    for m in range(3):
+        for g in range(G):
+            vals = [Fraction(float(x[m, perm[g * 128 + i]])) for i in range(128)]
+            a = max(abs(v) for v in vals)
+            if g < G - Go:
+                s = _fl(a / 7, 23, -126)
+                q = [max(-8, min(7, _round_half_even(_fl(v / s, 23, -126)))) for v in vals]
+                assert codes[m, g * 128:(g + 1) * 128].tolist() == q
+                assert Fraction(float(scales[m, g])) == s
+            else:
+                s = _fl(a / 119, 23, -126)
+                q8 = [max(-119, min(119, _round_half_even(_fl(v / s, 23, -126)))) for v in vals]
+                o = (G - Go + 2 * (g - (G - Go))) * 128
+                hi = codes[m, o:o + 128].astype(np.int64)
+                lo = codes[m, o + 128:o + 256].astype(np.int64)
+                assert (16 * hi + lo).tolist() == q8 and lo.min() >= -8 and lo.max() <= 7 and abs(hi).max() <= 7
+                assert Fraction(float(scales[m, o // 128])) == 16 * s and Fraction(float(scales[m, o // 128 + 1])) == s
+
+
+def test_reorder_quant_ordinary_groups_equal_the_plain_quantiser_on_the_gathered_tensor():
+    rng = np.random.default_rng(62)
+    x = rng.standard_normal((4, 512)).astype(np.float16)
+    perm = rng.permutation(512)
+    codes, scales = reo.reorder_quant(x, perm, 1)
+    q_ref, s_ref = orc.quant_act(np.ascontiguousarray(x[:, perm]))
+    assert np.array_equal(codes[:, :384], q_ref[:, :384]) and np.array_equal(scales[:, :3], s_ref[:, :3])
+    c0, s0 = reo.reorder_quant(x, perm, 0)                               # no outlier group: the plain quantiser
+    assert np.array_equal(c0, q_ref) and np.array_equal(s0, s_ref)
+    x[2] = 0
+    codes, scales = reo.reorder_quant(x, perm, 2)
+    assert not codes[2].any() and not scales[2].any()                    # zero row: zero scales, zero codes
+
+
+def test_reorder_quant_product_identity_with_duplicated_weight_groups():
+    """Integer check: with s = 1 in every group the draft-mode sum over the expanded
+    dimension equals the plain integer product of the 8-bit / 4-bit codes."""
+    rng = np.random.default_rng(63)
+    K, Go, N = 384, 1, 8
+    perm = rng.permutation(K)
+    x = np.zeros((2, K), dtype=np.float16)
+    xr = rng.integers(-7, 8, (2, K)).astype(np.float16)
+    xr[:, :256][:, [0, 128]] = 7                                         # a = 7 in the ordinary groups -> s = 1
+    xr[:, 256:] = rng.integers(-119, 120, (2, 128))
+    xr[:, 256] = 119                                                     # a = 119 in the outlier group -> s = 1
+    x[:, perm] = xr
+    w = rng.integers(-8, 8, (N, K))
+    codes, scales = reo.reorder_quant(x, perm, Go)
+    wx = reo.expand_weight_columns(w, perm, Go)
+    assert wx.shape == (N, K + 128)
+    deq = codes.astype(np.int64) * np.repeat(scales.astype(np.int64), 128, axis=1)
+    assert np.array_equal(deq @ wx.T, xr.astype(np.int64) @ w[:, perm].T)
+
+
+def test_reordering_lowers_the_draft_mode_error_on_outlier_channels():
+    codes, scales, x = synth.generic_case(55, 32, 256, 4096)
+    w = codes.astype(np.float64) * np.repeat(scales.astype(np.float64), 128, axis=1)
+    order = np.argsort(-np.abs(x.astype(np.float64)).mean(axis=0), kind="stable")
+    perm = np.concatenate([np.sort(order[128:]), np.sort(order[:128])])  # the 128 largest channels last
+    exact = x.astype(np.float64) @ w.T
+    qa, sa = orc.quant_act(x)
+    plain = np.linalg.norm((qa * np.repeat(sa.astype(np.float64), 128, axis=1)) @ w.T - exact) / np.linalg.norm(exact)
+    qr, sr = reo.reorder_quant(x, perm, 1)
+    wx = reo.expand_weight_columns(w, perm, 1)
+    reordered = np.linalg.norm((qr * np.repeat(sr.astype(np.float64), 128, axis=1)) @ wx.T - exact) / np.linalg.norm(exact)
+    assert reordered < 0.3 * plain, (plain, reordered)
