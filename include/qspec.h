@@ -153,6 +153,29 @@ int qspec_hadamard_quant(const void* x_f16, int M, int K, int group,
                          uint8_t* qa, float* sa, void* h_f16, void* stream);
 
 /*
+ * Reordering activation quantiser (paper Sec. 4.1 builds on existing 4-bit quantisers,
+ * one of which moves the few large channels together and keeps them in higher
+ * precision; the paper gives no detail, this form is this library's and needs no
+ * mixed-precision GEMM).  Position p of the reordered row takes channel perm[p]; the
+ * last n_outlier_groups groups of the reordered row are quantised to 239 levels,
+ *   a = max|x|, s = a / 119, q8 = clamp(rne(x / s), -119, 119)   (binary32, IEEE division)
+ * and written as two 4-bit groups, q8 = 16 hi + lo with lo in [-8,7], hi in [-7,7],
+ * with scales 16 s and s; all other groups as qspec_quant_act does.  Output: G' = G +
+ * n_outlier_groups groups (K' = 128 G'): the ordinary groups in order, then hi, lo of
+ * each outlier group.  The weights of the layer hold their columns in the same order,
+ * each outlier group twice in a row (prepared offline, before qspec_pack_weights with
+ * K'); qspec_gemm_w4a4 is then called with K'.
+ *   x_f16    fp16 [M,K];  perm  int32 [K], 16-byte aligned, a permutation of 0..K-1
+ *            (not checked; entries outside [0,K) are clamped);
+ *   0 <= n_outlier_groups <= K/128;
+ *   qa  out, M*K'/2 bytes;  sa  out, fp32 [M,G'];
+ *   h_f16    out, fp16 [M,K'] or NULL: the reordered row with a zero group after each
+ *            outlier group, i.e. the verify-mode input for the same weights.
+ */
+int qspec_reorder_quant(const void* x_f16, const int32_t* perm, int M, int K, int group,
+                        int n_outlier_groups, uint8_t* qa, float* sa, void* h_f16, void* stream);
+
+/*
  * Draft-mode product (paper Sec. 1: W4A4 runs on the low-precision matrix
  * units without dequantising to a higher precision):
  *   P[m,n,j] = sum_{k in group j} qa[m,k] * qw[n,k]             (int32, exact)

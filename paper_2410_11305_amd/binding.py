@@ -21,6 +21,7 @@ EXPORTS = (
     "qspec_gemm_w4a16", "qspec_gemm_w4a4_partials", "qspec_describe_kernel",
     "qspec_accept_workspace_bytes", "qspec_greedy_accept", "qspec_kv_overwrite",
     "qspec_rmsnorm_quant", "qspec_silu_mul_quant", "qspec_hadamard_quant",
+    "qspec_reorder_quant",
 )
 
 
@@ -78,6 +79,8 @@ def lib() -> ctypes.CDLL:
     L.qspec_silu_mul_quant.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp]
     L.qspec_hadamard_quant.restype = ci
     L.qspec_hadamard_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+    L.qspec_reorder_quant.restype = ci
+    L.qspec_reorder_quant.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp]
     _lib = L
     return L
 
@@ -225,6 +228,21 @@ def hadamard_quant(x: torch.Tensor, qa: torch.Tensor = None, sa: torch.Tensor = 
                                       _dev(qa, torch.uint8, "qa"), _dev(sa, torch.float32, "sa"),
                                       None if h is None else _dev(h, torch.float16, "h"), _stream()),
            "qspec_hadamard_quant")
+    return qa, sa, h
+
+
+def reorder_quant(x: torch.Tensor, perm: torch.Tensor, n_outlier_groups: int, qa: torch.Tensor = None,
+                  sa: torch.Tensor = None, h: torch.Tensor = None, want_h: bool = False, group: int = GROUP):
+    """Reordering quantiser: x fp16 [M,K], perm int32 [K] -> (qa uint8 [M,K'/2], sa fp32 [M,K'/128],
+    h fp16 [M,K'] or None) with K' = K + 128 * n_outlier_groups."""
+    M, K = x.shape
+    Kx = K + group * int(n_outlier_groups)
+    qa, sa, h = _quant_outputs(M, Kx, group, x.device, qa, sa, h, want_h)
+    _check(lib().qspec_reorder_quant(_dev(x, torch.float16, "x"), _dev(perm, torch.int32, "perm"), M, K, group,
+                                     int(n_outlier_groups), _dev(qa, torch.uint8, "qa"),
+                                     _dev(sa, torch.float32, "sa"),
+                                     None if h is None else _dev(h, torch.float16, "h"), _stream()),
+           "qspec_reorder_quant")
     return qa, sa, h
 
 

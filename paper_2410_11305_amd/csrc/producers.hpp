@@ -247,4 +247,98 @@ __global__ __launch_bounds__(256) void hadamard_quant_kernel(const uint4* __rest
   finish_unit(v, true, live, idx, qa_words, sa, h_out);
 }
 
+// ---- reordering quantiser: outlier channels last, their groups at 239 levels.
+// The reorder-and-keep-outliers-in-higher-precision quantisers that the paper
+// builds on (Sec. 4.1; no detail given) need a mixed-precision GEMM; this form does
+// not: an outlier group is quantised with s = a / 119, q8 in [-119, 119], and
+// written as two ordinary 4-bit groups, q8 = 16 hi + lo with lo in [-8, 7] and hi in
+// [-7, 7], scales 16 s and s, which multiply the same weight group (held twice in
+// the packed weights).  The draft-mode GEMM sees K' = K + 128 G_o input features.
+//   perm[p]: input channel at position p of the reordered row (entries are clamped
+//   to [0, K)); the last G_o groups of the reordered row are the outlier groups.
+// Output groups: the ordinary ones in order, then hi, lo of each outlier group.
+// One thread per 8 reordered positions, 16 lanes per group.  h_out (may be null):
+// fp16 [M][K'], the gathered row with a zero group after each outlier group, i.e.
+// the verify-mode input for the same expanded weights.
+__global__ __launch_bounds__(256) void reorder_quant_kernel(const uint16_t* __restrict__ x,
+                                                            const int* __restrict__ perm, int K, int Go,
+                                                            uint32_t* __restrict__ qa_words,
+                                                            float* __restrict__ sa, uint4* __restrict__ h_out,
+                                                            size_t n_words) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool live = idx < n_words;
+  const int K8 = K / 8, G = K / kGroup;
+  const size_t m = idx / (size_t)K8;
+  const int p8 = (int)(idx - m * (size_t)K8);
+  const int g = p8 >> 4, kw = p8 & 15;
+  float v[8];
+  v8h raw;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) raw[e] = (_Float16)0.0f;
+  if (live) {
+    const int4 c0 = *reinterpret_cast<const int4*>(perm + 8 * p8);
+    const int4 c1 = *reinterpret_cast<const int4*>(perm + 8 * p8 + 4);
+    const int ch[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+    const uint16_t* row = x + m * (size_t)K;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) raw[e] = __builtin_bit_cast(_Float16, row[min(max(ch[e], 0), K - 1)]);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (float)raw[e];
+  float a = 0.0f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a = fmaxf(a, fabsf(v[e]));
+  a = row16_max(a);
+  if (!live) return;
+
+  const int Gx = G + Go;                                  // groups of the output
+  const bool outlier = g >= G - Go;
+  const int og = outlier ? (G - Go) + 2 * (g - (G - Go)) : g;    // output group (the hi group of an outlier group)
+  // word position inside a group: k-word kw = 4i + kb is stored at 4kb + i
+  const int wpos = ((kw & 3) << 2) + (kw >> 2);
+  const size_t wbase = (m * (size_t)Gx + og) * 16 + wpos;
+  const size_t hbase = (m * (size_t)Gx + og) * 16 + kw;   // 16-byte pieces of the fp16 row
+  if (!outlier) {
+    const float s = a / 7.0f;
+    uint32_t w = 0;
+    if (a > 0.0f) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float t = rintf(v[e] / s);
+        t = fminf(fmaxf(t, -8.0f), 7.0f);
+        w |= ((uint32_t)(int)t & 0xFu) << (4 * nibble_pos(e));
+      }
+    }
+    qa_words[wbase] = w;
+    if (kw == 0) sa[m * (size_t)Gx + og] = s;
+    if (h_out != nullptr) h_out[hbase] = __builtin_bit_cast(uint4, raw);
+  } else {
+    const float s = a / 119.0f;
+    uint32_t whi = 0, wlo = 0;
+    if (a > 0.0f) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float t = rintf(v[e] / s);
+        t = fminf(fmaxf(t, -119.0f), 119.0f);
+        const int q8 = (int)t;
+        const int lo = ((q8 + 8) & 15) - 8;
+        const int hi = (q8 - lo) >> 4;                    // exact: q8 - lo is a multiple of 16
+        whi |= ((uint32_t)hi & 0xFu) << (4 * nibble_pos(e));
+        wlo |= ((uint32_t)lo & 0xFu) << (4 * nibble_pos(e));
+      }
+    }
+    qa_words[wbase] = whi;
+    qa_words[wbase + 16] = wlo;
+    if (kw == 0) {
+      sa[m * (size_t)Gx + og] = s * 16.0f;
+      sa[m * (size_t)Gx + og + 1] = s;
+    }
+    if (h_out != nullptr) {
+      const uint4 zero = {0u, 0u, 0u, 0u};
+      h_out[hbase] = __builtin_bit_cast(uint4, raw);
+      h_out[hbase + 16] = zero;
+    }
+  }
+}
+
 }  // namespace qspec

@@ -542,6 +542,22 @@ int qspec_hadamard_quant(const void* x_f16, int M, int K, int group,
   return launch_status();
 }
 
+int qspec_reorder_quant(const void* x_f16, const int32_t* perm, int M, int K, int group,
+                        int n_outlier_groups, uint8_t* qa, float* sa, void* h_f16, void* stream) {
+  if (!x_f16 || !perm || !qa || !sa) return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, kTileRows, K, group)) return st;
+  if (n_outlier_groups < 0 || n_outlier_groups > K / kGroup) return QSPEC_ERR_SHAPE;
+  if (int st = check_shape(M, kTileRows, K + kGroup * n_outlier_groups, group)) return st;
+  if (misaligned(x_f16) || misaligned(perm) || misaligned(qa) || misaligned(sa) || misaligned(h_f16))
+    return QSPEC_ERR_ALIGN;
+  if (int st = check_device()) return st;
+  const size_t n_words = (size_t)M * K / 8;
+  hipLaunchKernelGGL(reorder_quant_kernel, dim3(blocks_for(n_words, 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint16_t*>(x_f16), perm, K,
+                     n_outlier_groups, reinterpret_cast<uint32_t*>(qa), sa, static_cast<uint4*>(h_f16), n_words);
+  return launch_status();
+}
+
 int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int M, int N, int K, int group,
                     void* y_f16, void* workspace, size_t workspace_bytes, void* stream) {
   if (!packed || !qa || !sa || !y_f16) return QSPEC_ERR_NULL;
