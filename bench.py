@@ -368,6 +368,29 @@ def main() -> int:
         "rmsnorm_rotate_quant_us": round(per_call(lambda: B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1], rotate=True)), 3),
         "silu_mul_rotate_quant_us": round(per_call(lambda: B.silu_mul_quant(pgu, pq_i[0], pq_i[1], rotate=True)), 3),
     }
+    # the reordering quantiser (outlier channels last, one outlier group at 239 levels as two 4-bit
+    # groups) and what the extra group costs the draft-mode GEMM of the first layer
+    order = np.argsort(-np.abs(px_h.astype(np.float64)).mean(axis=0), kind="stable")
+    pperm = to(np.concatenate([np.sort(order[128:]), np.sort(order[:128])]).astype(np.int32))
+    Kx = Kh + 128
+    pq_x = (torch.empty((Md, Kx // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Kx // 128), dtype=torch.float32, device=dev))
+    fused_producers["reorder_quant_hidden_us"] = round(per_call(lambda: B.reorder_quant(px, pperm, 1, pq_x[0], pq_x[1])), 3)
+    lin0 = lins[0]
+    blobs_x = []
+    for l in range(L):
+        cx = torch.randint(-8, 8, (lin0.N, Kx), dtype=torch.int8, device=dev, generator=gen)
+        sx = (torch.rand((lin0.N, Kx // 128), device=dev, generator=gen) * 0.008 + 0.002).half()
+        blobs_x.append(B.pack_weights(cx, sx))
+        del cx, sx
+    B.reorder_quant(px, pperm, 1, pq_x[0], pq_x[1])
+    B.quant_act(px, pq_h[0], pq_h[1])
+    y0 = torch.empty((Md, lin0.N), dtype=torch.float16, device=dev)
+    ws_x = B.alloc_workspace(max(B.workspace_bytes(Md, lin0.N, Kx), B.workspace_bytes(Md, lin0.N, Kh), 16))
+    t_kx = time_runner(make_runner(lambda: [B.gemm_w4a4(b, pq_x[0], pq_x[1], lin0.N, y=y0, workspace=ws_x) for b in blobs_x]), reps, 2) / L
+    t_k = time_runner(make_runner(lambda: [B.gemm_w4a4(blobs[l][0], pq_h[0], pq_h[1], lin0.N, y=y0, workspace=ws_x) for l in range(L)]), reps, 2) / L
+    fused_producers["draft_gemm_first_layer_us"] = {"K": round(t_k * 1e6, 3), "K_plus_one_outlier_group": round(t_kx * 1e6, 3)}
+    del blobs_x
+
     fused_producers["silu_mul_quant_GBps"] = round((Md * Ii * 4 + Md * Ii // 2 + Md * (Ii // 128) * 4)
                                                    / fused_producers["silu_mul_quant_us"] / 1e3, 1)
 
