@@ -58,8 +58,10 @@ def main() -> int:
     ap.add_argument("--vendor-context", action="store_true",
                     help="also time torch.matmul (the vendor library's plain fp16 GEMM, fp16 weights, no quantisation) "
                          "on this configuration's verify-mode shapes: a yardstick for what the machine sustains, not a target")
+    ap.add_argument("--prefill", action="store_true",
+                    help="also time both modes at 1024 and 2048 tokens (prefill-sized M) in extra_rows_M256_M512")
     ap.add_argument("--no-extra", action="store_true",
-                    help="skip the rows at 256 and 512 tokens and the verify-mode pass at the draft M (profiling runs: their "
+                    help="skip the rows at 256 and 512 tokens, the verify-mode pass at the draft M and the fused producers (profiling runs: their "
                          "launches would mix into the kernel statistics)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -283,7 +285,7 @@ def main() -> int:
     # configuration drafts more than 128 tokens; these rows show the draft-mode kernel in
     # the matrix-bound regime next to the verify-mode kernel at the same shape)
     extra = {}
-    for Mx in (() if args.no_extra else (256, 512)):
+    for Mx in (() if args.no_extra else ((256, 512, 1024, 2048) if args.prefill else (256, 512))):
         xx = [torch.randn((Mx, lin.K), device=dev, generator=gen).half() for lin in lins]
         qx = [B.quant_act(t) for t in xx]
         yx = [torch.empty((Mx, lin.N), dtype=torch.float16, device=dev) for lin in lins]
@@ -335,64 +337,70 @@ def main() -> int:
                        reps, 2) / n_rep_small
     acc_bytes = Bn * rows * V * 2 + Bn * (rows - 1) * 4 + Bn * (rows + 1) * 4
     kv_bytes = int((n_acc.sum().item() + Bn) * kvD * 2 * 2)
-    # ---- the fused producers of draft-mode activations (RMSNorm + quantiser, SiLU*up +
-    # quantiser): beside the step as well, against the quantiser alone on the same shape
-    # and against the unfused pair with torch's own producer kernels in front of it
-    px_h, pw_h, pgu_h = synth.producer_inputs(args.config)
-    px, pw, pgu = to(px_h), to(pw_h), to(pgu_h)
-    Kh, Ii = px.shape[1], pgu.shape[1] // 2
-    pq_h = (torch.empty((Md, Kh // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Kh // 128), dtype=torch.float32, device=dev))
-    pq_i = (torch.empty((Md, Ii // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Ii // 128), dtype=torch.float32, device=dev))
-    ph = torch.empty((Md, Kh), dtype=torch.float16, device=dev)
-    pi = torch.empty((Md, Ii), dtype=torch.float16, device=dev)
 
-    def torch_rms():
-        return torch.nn.functional.rms_norm(px, (Kh,), pw, synth.RMS_EPS)
+    def time_fused_producers():
+        # ---- the fused producers of draft-mode activations (RMSNorm + quantiser, SiLU*up +
+        # quantiser): beside the step as well, against the quantiser alone on the same shape
+        # and against the unfused pair with torch's own producer kernels in front of it
+        px_h, pw_h, pgu_h = synth.producer_inputs(args.config)
+        px, pw, pgu = to(px_h), to(pw_h), to(pgu_h)
+        Kh, Ii = px.shape[1], pgu.shape[1] // 2
+        pq_h = (torch.empty((Md, Kh // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Kh // 128), dtype=torch.float32, device=dev))
+        pq_i = (torch.empty((Md, Ii // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Ii // 128), dtype=torch.float32, device=dev))
+        ph = torch.empty((Md, Kh), dtype=torch.float16, device=dev)
+        pi = torch.empty((Md, Ii), dtype=torch.float16, device=dev)
 
-    def torch_silu():
-        return torch.nn.functional.silu(pgu[:, :Ii]) * pgu[:, Ii:]
+        def torch_rms():
+            return torch.nn.functional.rms_norm(px, (Kh,), pw, synth.RMS_EPS)
 
-    def per_call(f):
-        return time_runner(make_runner(lambda: [f() for _ in range(n_rep_small)]), reps, 2) / n_rep_small * 1e6
+        def torch_silu():
+            return torch.nn.functional.silu(pgu[:, :Ii]) * pgu[:, Ii:]
 
-    fused_producers = {
-        "M": Md, "hidden": Kh, "intermediate": Ii,
-        "rmsnorm_quant_us": round(per_call(lambda: B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1])), 3),
-        "quant_act_alone_hidden_us": round(per_call(lambda: B.quant_act(ph, pq_h[0], pq_h[1])), 3),
-        "torch_rms_norm_then_quant_act_us": round(per_call(lambda: B.quant_act(torch_rms(), pq_h[0], pq_h[1])), 3),
-        "silu_mul_quant_us": round(per_call(lambda: B.silu_mul_quant(pgu, pq_i[0], pq_i[1])), 3),
-        "quant_act_alone_intermediate_us": round(per_call(lambda: B.quant_act(pi, pq_i[0], pq_i[1])), 3),
-        "torch_silu_mul_then_quant_act_us": round(per_call(lambda: B.quant_act(torch_silu(), pq_i[0], pq_i[1])), 3),
-        # with the per-group Hadamard rotation in front of the quantiser
-        "hadamard_quant_hidden_us": round(per_call(lambda: B.hadamard_quant(ph, pq_h[0], pq_h[1])), 3),
-        "rmsnorm_rotate_quant_us": round(per_call(lambda: B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1], rotate=True)), 3),
-        "silu_mul_rotate_quant_us": round(per_call(lambda: B.silu_mul_quant(pgu, pq_i[0], pq_i[1], rotate=True)), 3),
-    }
-    # the reordering quantiser (outlier channels last, one outlier group at 239 levels as two 4-bit
-    # groups) and what the extra group costs the draft-mode GEMM of the first layer
-    order = np.argsort(-np.abs(px_h.astype(np.float64)).mean(axis=0), kind="stable")
-    pperm = to(np.concatenate([np.sort(order[128:]), np.sort(order[:128])]).astype(np.int32))
-    Kx = Kh + 128
-    pq_x = (torch.empty((Md, Kx // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Kx // 128), dtype=torch.float32, device=dev))
-    fused_producers["reorder_quant_hidden_us"] = round(per_call(lambda: B.reorder_quant(px, pperm, 1, pq_x[0], pq_x[1])), 3)
-    lin0 = lins[0]
-    blobs_x = []
-    for l in range(L):
-        cx = torch.randint(-8, 8, (lin0.N, Kx), dtype=torch.int8, device=dev, generator=gen)
-        sx = (torch.rand((lin0.N, Kx // 128), device=dev, generator=gen) * 0.008 + 0.002).half()
-        blobs_x.append(B.pack_weights(cx, sx))
-        del cx, sx
-    B.reorder_quant(px, pperm, 1, pq_x[0], pq_x[1])
-    B.quant_act(px, pq_h[0], pq_h[1])
-    y0 = torch.empty((Md, lin0.N), dtype=torch.float16, device=dev)
-    ws_x = B.alloc_workspace(max(B.workspace_bytes(Md, lin0.N, Kx), B.workspace_bytes(Md, lin0.N, Kh), 16))
-    t_kx = time_runner(make_runner(lambda: [B.gemm_w4a4(b, pq_x[0], pq_x[1], lin0.N, y=y0, workspace=ws_x) for b in blobs_x]), reps, 2) / L
-    t_k = time_runner(make_runner(lambda: [B.gemm_w4a4(blobs[l][0], pq_h[0], pq_h[1], lin0.N, y=y0, workspace=ws_x) for l in range(L)]), reps, 2) / L
-    fused_producers["draft_gemm_first_layer_us"] = {"K": round(t_k * 1e6, 3), "K_plus_one_outlier_group": round(t_kx * 1e6, 3)}
-    del blobs_x
+        def per_call(f):
+            return time_runner(make_runner(lambda: [f() for _ in range(n_rep_small)]), reps, 2) / n_rep_small * 1e6
 
-    fused_producers["silu_mul_quant_GBps"] = round((Md * Ii * 4 + Md * Ii // 2 + Md * (Ii // 128) * 4)
-                                                   / fused_producers["silu_mul_quant_us"] / 1e3, 1)
+        fused_producers = {
+            "M": Md, "hidden": Kh, "intermediate": Ii,
+            "rmsnorm_quant_us": round(per_call(lambda: B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1])), 3),
+            "quant_act_alone_hidden_us": round(per_call(lambda: B.quant_act(ph, pq_h[0], pq_h[1])), 3),
+            "torch_rms_norm_then_quant_act_us": round(per_call(lambda: B.quant_act(torch_rms(), pq_h[0], pq_h[1])), 3),
+            "silu_mul_quant_us": round(per_call(lambda: B.silu_mul_quant(pgu, pq_i[0], pq_i[1])), 3),
+            "quant_act_alone_intermediate_us": round(per_call(lambda: B.quant_act(pi, pq_i[0], pq_i[1])), 3),
+            "torch_silu_mul_then_quant_act_us": round(per_call(lambda: B.quant_act(torch_silu(), pq_i[0], pq_i[1])), 3),
+            # with the per-group Hadamard rotation in front of the quantiser
+            "hadamard_quant_hidden_us": round(per_call(lambda: B.hadamard_quant(ph, pq_h[0], pq_h[1])), 3),
+            "rmsnorm_rotate_quant_us": round(per_call(lambda: B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1], rotate=True)), 3),
+            "silu_mul_rotate_quant_us": round(per_call(lambda: B.silu_mul_quant(pgu, pq_i[0], pq_i[1], rotate=True)), 3),
+        }
+        # the reordering quantiser (outlier channels last, one outlier group at 239 levels as two 4-bit
+        # groups) and what the extra group costs the draft-mode GEMM of the first layer
+        order = np.argsort(-np.abs(px_h.astype(np.float64)).mean(axis=0), kind="stable")
+        pperm = to(np.concatenate([np.sort(order[128:]), np.sort(order[:128])]).astype(np.int32))
+        Kx = Kh + 128
+        pq_x = (torch.empty((Md, Kx // 2), dtype=torch.uint8, device=dev), torch.empty((Md, Kx // 128), dtype=torch.float32, device=dev))
+        fused_producers["reorder_quant_hidden_us"] = round(per_call(lambda: B.reorder_quant(px, pperm, 1, pq_x[0], pq_x[1])), 3)
+        lin0 = lins[0]
+        blobs_x = []
+        for l in range(L):
+            cx = torch.randint(-8, 8, (lin0.N, Kx), dtype=torch.int8, device=dev, generator=gen)
+            sx = (torch.rand((lin0.N, Kx // 128), device=dev, generator=gen) * 0.008 + 0.002).half()
+            blobs_x.append(B.pack_weights(cx, sx))
+            del cx, sx
+        B.reorder_quant(px, pperm, 1, pq_x[0], pq_x[1])
+        B.quant_act(px, pq_h[0], pq_h[1])
+        y0 = torch.empty((Md, lin0.N), dtype=torch.float16, device=dev)
+        ws_x = B.alloc_workspace(max(B.workspace_bytes(Md, lin0.N, Kx), B.workspace_bytes(Md, lin0.N, Kh), 16))
+        t_kx = time_runner(make_runner(lambda: [B.gemm_w4a4(b, pq_x[0], pq_x[1], lin0.N, y=y0, workspace=ws_x) for b in blobs_x]), reps, 2) / L
+        t_k = time_runner(make_runner(lambda: [B.gemm_w4a4(blobs[l][0], pq_h[0], pq_h[1], lin0.N, y=y0, workspace=ws_x) for l in range(L)]), reps, 2) / L
+        fused_producers["draft_gemm_first_layer_us"] = {"K": round(t_k * 1e6, 3), "K_plus_one_outlier_group": round(t_kx * 1e6, 3)}
+        del blobs_x
+
+        fused_producers["silu_mul_quant_GBps"] = round((Md * Ii * 4 + Md * Ii // 2 + Md * (Ii // 128) * 4)
+                                                       / fused_producers["silu_mul_quant_us"] / 1e3, 1)
+        return fused_producers
+
+    # (their quantiser and GEMM launches would mix into the kernel statistics of a profiling run)
+    fused_producers = None if args.no_extra else time_fused_producers()
 
     after_verify = {
         "greedy_accept": dict(B=Bn, gamma=rows - 1, V=V, us=round(t_acc * 1e6, 3), launches=2,
