@@ -89,3 +89,29 @@ def test_accept_entries_validate_without_device():
     assert L.qspec_kv_overwrite(a, a, a, 1, 1, 16, 0, a, None) == B.ERR_SHAPE
     assert L.qspec_kv_overwrite(a, None, a, 1, 1, 16, 4, a, None) == B.ERR_NULL
     assert L.qspec_kv_overwrite(a, a, a, 1, 1, 16, 4, a + 4, None) == B.ERR_ALIGN
+
+
+def test_producer_and_outlier_entries_validate_without_device():
+    L = B.lib()
+    a = 4096
+    eps = 1e-5
+    assert L.qspec_rmsnorm_quant(None, a, eps, 1, 128, 128, 0, a, a, None, None) == B.ERR_NULL
+    assert L.qspec_rmsnorm_quant(a, None, eps, 1, 128, 128, 0, a, a, None, None) == B.ERR_NULL
+    assert L.qspec_rmsnorm_quant(a, a, eps, 0, 128, 128, 0, a, a, None, None) == B.ERR_SHAPE
+    assert L.qspec_rmsnorm_quant(a, a, eps, 1, 192, 128, 0, a, a, None, None) == B.ERR_SHAPE
+    assert L.qspec_rmsnorm_quant(a, a, -1.0, 1, 128, 128, 0, a, a, None, None) == B.ERR_SHAPE
+    assert L.qspec_rmsnorm_quant(a, a, float("inf"), 1, 128, 128, 0, a, a, None, None) == B.ERR_SHAPE
+    assert L.qspec_rmsnorm_quant(a, a, eps, 1, 128, 128, 2, a, a, None, None) == B.ERR_SHAPE        # rotate is 0 or 1
+    assert L.qspec_rmsnorm_quant(a, a + 8, eps, 1, 128, 128, 0, a, a, None, None) == B.ERR_ALIGN
+    assert L.qspec_rmsnorm_quant(a, a, eps, 1, 128, 128, 0, a, a, a + 2, None) == B.ERR_ALIGN
+    assert L.qspec_silu_mul_quant(None, 1, 128, 128, 0, a, a, None, None) == B.ERR_NULL
+    assert L.qspec_silu_mul_quant(a, 1, 100, 128, 0, a, a, None, None) == B.ERR_SHAPE
+    assert L.qspec_silu_mul_quant(a, 1, 128, 128, -1, a, a, None, None) == B.ERR_SHAPE
+    assert L.qspec_silu_mul_quant(a, 1, 128, 128, 0, a + 4, a, None, None) == B.ERR_ALIGN
+    assert L.qspec_hadamard_quant(a, 1, 128, 128, None, a, None, None) == B.ERR_NULL
+    assert L.qspec_hadamard_quant(a, 1, 128, 64, a, a, None, None) == B.ERR_SHAPE
+    assert L.qspec_hadamard_quant(a + 2, 1, 128, 128, a, a, None, None) == B.ERR_ALIGN
+    assert L.qspec_reorder_quant(a, None, 1, 128, 128, 1, a, a, None, None) == B.ERR_NULL
+    assert L.qspec_reorder_quant(a, a, 1, 128, 128, 2, a, a, None, None) == B.ERR_SHAPE             # more outlier groups than groups
+    assert L.qspec_reorder_quant(a, a, 1, 128, 128, -1, a, a, None, None) == B.ERR_SHAPE
+    assert L.qspec_reorder_quant(a, a + 4, 1, 128, 128, 1, a, a, None, None) == B.ERR_ALIGN
