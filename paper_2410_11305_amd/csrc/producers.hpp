@@ -15,6 +15,10 @@
 // x * w is exact in binary32 (two 11-bit significands).  Both kernels are bound
 // by launch latency at draft sizes; the binary64 work is a few thousand
 // instructions per wavefront.
+//
+// Further down: the two outlier-aware forms of the quantiser itself, a Hadamard
+// rotation of every group (also available behind both producers) and a reordering
+// quantiser that carries outlier groups at 239 levels as two 4-bit groups.
 #pragma once
 #include "common.hpp"
 #include "quant_act.hpp"
