@@ -395,6 +395,30 @@ def main() -> int:
         fused_producers["draft_gemm_first_layer_us"] = {"K": round(t_k * 1e6, 3), "K_plus_one_outlier_group": round(t_kx * 1e6, 3)}
         del blobs_x
 
+        # the MLP of a decoder block as the draft pass runs it: RMSNorm -> gate/up -> SiLU*up -> down,
+        # fused producers (4 launches) against torch's producers + the plain quantiser (6 launches)
+        i_gu = next(i for i, l in enumerate(lins) if l.name == "gate_up") if len(lins) == 4 else None
+        if i_gu is not None and lins[i_gu].N == 2 * Ii and lins[3].K == Ii and lins[i_gu].K == Kh:
+            ygu = torch.empty((Md, 2 * Ii), dtype=torch.float16, device=dev)
+            ydn = torch.empty((Md, lins[3].N), dtype=torch.float16, device=dev)
+
+            def mlp_fused():
+                for l in range(L):
+                    B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1])
+                    B.gemm_w4a4(blobs[l][i_gu], pq_h[0], pq_h[1], 2 * Ii, y=ygu, workspace=ws)
+                    B.silu_mul_quant(ygu, pq_i[0], pq_i[1])
+                    B.gemm_w4a4(blobs[l][3], pq_i[0], pq_i[1], lins[3].N, y=ydn, workspace=ws)
+
+            def mlp_unfused():
+                for l in range(L):
+                    B.quant_act(torch_rms(), pq_h[0], pq_h[1])
+                    B.gemm_w4a4(blobs[l][i_gu], pq_h[0], pq_h[1], 2 * Ii, y=ygu, workspace=ws)
+                    B.quant_act(torch.nn.functional.silu(ygu[:, :Ii]) * ygu[:, Ii:], pq_i[0], pq_i[1])
+                    B.gemm_w4a4(blobs[l][3], pq_i[0], pq_i[1], lins[3].N, y=ydn, workspace=ws)
+
+            fused_producers["draft_mlp_block_us"] = {
+                "fused_producers": round(time_runner(make_runner(mlp_fused), reps, 2) / L * 1e6, 2),
+                "torch_producers_plus_quant_act": round(time_runner(make_runner(mlp_unfused), reps, 2) / L * 1e6, 2)}
         fused_producers["silu_mul_quant_GBps"] = round((Md * Ii * 4 + Md * Ii // 2 + Md * (Ii // 128) * 4)
                                                        / fused_producers["silu_mul_quant_us"] / 1e3, 1)
         return fused_producers
