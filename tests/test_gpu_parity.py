@@ -445,3 +445,47 @@ def test_bad_arguments_are_refused_on_device(env):
     assert L.qspec_gemm_w4a16(blob.data_ptr(), xd.data_ptr(), M, N + 8, K, 128, y.data_ptr(), None, 0, None) == B.ERR_SHAPE
     with pytest.raises(B.QSpecError):
         B.quant_act(xd[:, :200].contiguous())
+
+
+# ------------------------------------------------------------------ many shapes
+def test_random_shapes_take_every_plan_and_match(env):
+    """150 seeded shapes across the planner's regimes (streaming kernels with 1..6 tiles,
+    K-slices, token-row blocks, the wide one-round plans, tiled kernels of every size
+    class): both modes against the oracle, and the set of kernels that ran is reported."""
+    torch, B = env
+    rng = np.random.default_rng(2024)
+    seen = {}
+    worst = (0.0, None)
+    for case in range(150):
+        regime = case % 5
+        if regime == 0:      # decoding batch, wide and narrow layers
+            M, N, K = int(rng.integers(1, 33)), 16 * int(rng.integers(1, 700)), 128 * int(rng.integers(1, 24))
+        elif regime == 1:    # mid batch
+            M, N, K = int(rng.integers(33, 130)), 16 * int(rng.integers(1, 400)), 128 * int(rng.integers(1, 16))
+        elif regime == 2:    # many tokens
+            M, N, K = int(rng.integers(130, 700)), 16 * int(rng.integers(1, 80)), 128 * int(rng.integers(1, 10))
+        elif regime == 3:    # long K, few columns (K-slices)
+            M, N, K = int(rng.integers(1, 140)), 16 * int(rng.integers(1, 24)), 128 * int(rng.integers(24, 90))
+        else:                # tiny
+            M, N, K = int(rng.integers(1, 20)), 16 * int(rng.integers(1, 6)), 128 * int(rng.integers(1, 4))
+        while M * N * K > 3e8:
+            N = max(16, N // 2 // 16 * 16)
+        codes, scales, x = synth.generic_case(9000 + case, M, N, K)
+        blob = B.pack_weights(dev(torch, codes), dev(torch, scales))
+        xd = dev(torch, x)
+        qa, sa = B.quant_act(xd)
+        y4 = B.gemm_w4a4(blob, qa, sa, N).cpu().numpy()
+        y16 = B.gemm_w4a16(blob, xd, N).cpu().numpy()
+        q_ref, s_ref = orc.quant_act(x)
+        e4 = rel_err(y4, orc.gemm_w4a4(q_ref, s_ref, codes, scales))
+        e16 = rel_err(y16, orc.gemm_w4a16(x, codes, scales))
+        for w4a4 in (True, False):
+            k = B.describe_kernel(w4a4, M, N, K)
+            seen[k] = seen.get(k, 0) + 1
+        if max(e4, e16) > worst[0]:
+            worst = (max(e4, e16), (M, N, K))
+        assert e4 <= TOL and e16 <= TOL, (case, M, N, K, e4, e16, B.describe_kernel(True, M, N, K), B.describe_kernel(False, M, N, K))
+    print("worst", worst, flush=True)
+    for k in sorted(seen):
+        print(f"  {seen[k]:4d}  {k}", flush=True)
+    assert len(seen) >= 12            # the sample reaches a broad set of instances
