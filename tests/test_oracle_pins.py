@@ -871,3 +871,102 @@ def test_reordering_lowers_the_draft_mode_error_on_outlier_channels():
     wx = reo.expand_weight_columns(w, perm, 1)
     reordered = np.linalg.norm((qr * np.repeat(sr.astype(np.float64), 128, axis=1)) @ wx.T - exact) / np.linalg.norm(exact)
     assert reordered < 0.3 * plain, (plain, reordered)
+
+
+# ---------------------------------------------------------------- the pins do bite
+def _caught(monkeypatch, module, name, mutant, pins):
+    """True if at least one of the pin tests fails once `module.name` is replaced by `mutant`."""
+    with monkeypatch.context() as mp:
+        mp.setattr(module, name, mutant)
+        for pin in pins:
+            try:
+                pin()
+            except AssertionError:
+                return True
+            except Exception:
+                return True
+    return False
+
+
+def test_planted_mistakes_in_the_newer_oracles_fail_their_pins(monkeypatch):
+    f32, f64, f16 = np.float32, np.float64, np.float16
+
+    # ---- RMSNorm
+    def rms_variant(eps_outside=False, mean_abs=False, drop_weight=False):
+        def fn(x, w, eps):
+            x64 = x.astype(f64)
+            stat = np.mean(np.abs(x64), axis=1) ** 2 if mean_abs else np.sum(x64 * x64, axis=1) / x.shape[1]
+            e = f64(f32(eps))
+            r = (1.0 / (np.sqrt(stat) + e) if eps_outside else 1.0 / np.sqrt(stat + e)).astype(f32)
+            t = x.astype(f32) * (1.0 if drop_weight else w.astype(f32)[None, :])
+            return (t * r[:, None]).astype(f32).astype(f16)
+        return fn
+    rms_pins = [test_rmsnorm_vs_exact_rationals, test_rmsnorm_closed_forms, test_rmsnorm_vs_torch_cpu_float64]
+    assert not _caught(monkeypatch, prod, "rmsnorm_f16", rms_variant(), rms_pins)          # the faithful copy passes
+    for kw in (dict(eps_outside=True), dict(mean_abs=True), dict(drop_weight=True)):
+        assert _caught(monkeypatch, prod, "rmsnorm_f16", rms_variant(**kw), rms_pins), kw
+
+    # ---- SiLU * up
+    def silu_variant(sign=-1.0, swap=False, sigmoid_only=False):
+        def fn(gu):
+            I = gu.shape[1] // 2
+            g, u = (gu[:, I:], gu[:, :I]) if swap else (gu[:, :I], gu[:, I:])
+            g = g.astype(f64)
+            with np.errstate(over="ignore", invalid="ignore"):
+                s = ((1.0 if sigmoid_only else g) / (1.0 + np.exp(sign * g))).astype(f32)
+            return (s * u.astype(f32)).astype(f32).astype(f16)
+        return fn
+    silu_pins = [test_silu_mul_vs_high_precision_decimal, test_silu_mul_closed_forms_and_column_order,
+                 test_silu_mul_vs_torch_cpu_float64]
+    assert not _caught(monkeypatch, prod, "silu_mul_f16", silu_variant(), silu_pins)
+    for kw in (dict(sign=1.0), dict(swap=True), dict(sigmoid_only=True)):
+        assert _caught(monkeypatch, prod, "silu_mul_f16", silu_variant(**kw), silu_pins), kw
+
+    # ---- rotation
+    def had_variant(scale=0.125, reversed_difference=False, block=128):
+        def fn(x):
+            M, K = x.shape
+            v = x.astype(f32).reshape(M, K // block, block)
+            h = 1
+            while h < block:
+                p = v.reshape(M, K // block, block // (2 * h), 2, h)
+                lo, hi = p[..., 0, :], p[..., 1, :]
+                v = np.stack([lo + hi, (hi - lo) if reversed_difference else (lo - hi)], axis=-2)
+                h *= 2
+            return (v.reshape(M, K) * f32(scale)).astype(f16)
+        return fn
+    had_pins = [test_hadamard_equals_the_matrix_product_where_sums_are_exact, test_hadamard_entries_on_one_hot_rows,
+                test_hadamard_groups_are_independent_and_twice_is_doubling]
+    assert not _caught(monkeypatch, rot, "hadamard128_f16", had_variant(), had_pins)
+    for kw in (dict(scale=1.0 / 16), dict(reversed_difference=True), dict(block=64)):
+        assert _caught(monkeypatch, rot, "hadamard128_f16", had_variant(**kw), had_pins), kw
+
+    # ---- reordering quantiser: planted through its constants and its digit split
+    reo_pins = [test_reorder_quant_hand_worked_group, test_reorder_quant_vs_exact_rationals,
+                test_reorder_quant_product_identity_with_duplicated_weight_groups]
+    with monkeypatch.context() as mp:
+        mp.setattr(reo, "LEVELS", 127)
+        caught = False
+        for pin in reo_pins:
+            try:
+                pin()
+            except AssertionError:
+                caught = True
+                break
+        assert caught
+    original = reo.reorder_quant
+
+    def swapped_digits(x, perm, Go):
+        codes, scales = original(x, perm, Go)
+        G = x.shape[1] // 128
+        c = codes.reshape(x.shape[0], G + Go, 128).copy()
+        for t in range(Go):
+            a = G - Go + 2 * t
+            c[:, [a, a + 1]] = c[:, [a + 1, a]]
+        return c.reshape(codes.shape), scales
+    assert _caught(monkeypatch, reo, "reorder_quant", swapped_digits, reo_pins)
+
+    def inverse_permutation(x, perm, Go):
+        return original(x, np.argsort(np.asarray(perm)), Go)
+    assert _caught(monkeypatch, reo, "reorder_quant", inverse_permutation, reo_pins)
+    assert not _caught(monkeypatch, reo, "reorder_quant", original, reo_pins)
