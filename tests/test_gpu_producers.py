@@ -187,6 +187,21 @@ def test_rotated_activations_give_the_same_product_with_rotated_weights(env):
     assert torch.equal(y_plain, y_rot)
 
 
+def test_random_shapes_all_producers(env):
+    """60 seeded shapes: every fused kernel, with and without the rotation, against the oracles."""
+    rng = np.random.default_rng(31)
+    for case in range(60):
+        M = int(rng.integers(1, 200))
+        K = 128 * int(rng.integers(1, 70))
+        I = 128 * int(rng.integers(1, 40))
+        x, w, gu = synth.producer_case(800 + case, M, K, I)
+        rotate = bool(case & 1)
+        run_rmsnorm(env, x, w, [1e-6, 1e-5, 0.25][case % 3], want_h=bool(case & 2), rotate=rotate)
+        run_silu(env, gu, want_h=bool(case & 2), rotate=rotate)
+        if case % 4 == 0:
+            run_hadamard(env, x)
+
+
 def test_bad_arguments_are_refused(env):
     torch, B = env
     x = torch.zeros((2, 256), dtype=torch.float16, device="cuda")
