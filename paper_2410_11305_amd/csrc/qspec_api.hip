@@ -415,7 +415,7 @@ const char* qspec_status_string(int status) {
   switch (status) {
     case QSPEC_OK: return "ok";
     case QSPEC_ERR_NULL: return "null pointer";
-    case QSPEC_ERR_SHAPE: return "unsupported shape (need group == 128, K % 128 == 0, N % 16 == 0, M >= 1)";
+    case QSPEC_ERR_SHAPE: return "unsupported shape or argument value (need group == 128, K % 128 == 0, N % 16 == 0, M >= 1, every buffer below 2 GiB; see the entry point for its other arguments)";
     case QSPEC_ERR_ALIGN: return "pointer not 16-byte aligned";
     case QSPEC_ERR_WORKSPACE: return "workspace too small";
     case QSPEC_ERR_HIP: return "HIP runtime error";
