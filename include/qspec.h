@@ -60,7 +60,7 @@ typedef enum {
   QSPEC_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned              */
   QSPEC_ERR_WORKSPACE = 4,   /* workspace smaller than qspec_workspace_bytes  */
   QSPEC_ERR_HIP = 5,         /* the HIP runtime refused the launch            */
-  QSPEC_ERR_UNSUPPORTED = 6  /* the current device is not gfx950              */
+  QSPEC_ERR_UNSUPPORTED = 6  /* not gfx950, or a forced plan has no kernel     */
 } qspec_status;
 
 /* Human-readable name of a status code (static storage, never NULL). */
@@ -250,6 +250,23 @@ int qspec_greedy_accept(const void* logits_f16, const int32_t* draft_tokens, int
  */
 int qspec_kv_overwrite(const void* kv_verify_f16, const int32_t* n_accept, const int32_t* pos,
                        int B, int gamma, int D, int S, void* cache_f16, void* stream);
+
+/*
+ * Debug entry (benchmark A/B and tests): force the kernel plan the GEMM entry points
+ * and qspec_workspace_bytes use, instead of the library's own choice.  `name` is one of
+ *   "QSPEC_KERNEL"            value "generic": untiled reference kernels for M > 32
+ *   "QSPEC_STREAM_W4A4",  "QSPEC_STREAM_W4A16"   value "NT,S" or "NT,S,MS": tiles per
+ *                             workgroup, K-slices, token-row blocks of the streaming kernels
+ *   "QSPEC_STREAM_MAX_W4A4"   largest M the draft-mode streaming kernel takes (32..128)
+ *   "QSPEC_TILE_W4A4",    "QSPEC_TILE_W4A16"     value "shape,S": workgroup shape, K-slices
+ * `value` NULL (or unparsable) clears that override; both are host strings.  The same
+ * names are read from the environment once, at the library's first use; no entry point
+ * reads the environment afterwards.  A forced plan that names no existing kernel instance
+ * falls back to the library's choice or makes the GEMM call return
+ * QSPEC_ERR_UNSUPPORTED.  Process-wide state: do not call it while another thread is
+ * inside a GEMM entry point.  Returns QSPEC_ERR_SHAPE for an unknown name.
+ */
+int qspec_debug_set_plan(const char* name, const char* value);
 
 /*
  * Debug entry: name of the device kernel the GEMM entry points select for an

@@ -172,5 +172,7 @@ def gemm_w4a16_columns(x, qw, sw, cols, group: int = GROUP) -> np.ndarray:
 
 
 def gemm_w4a4_columns(qa, sa, qw, sw, cols, group: int = GROUP) -> np.ndarray:
+    """gemm_w4a4 restricted to the output columns `cols`, in the order given (column n
+    of the product uses only row n of the weight codes and scales)."""
     cols = np.asarray(cols)
     return gemm_w4a4(qa, sa, np.asarray(qw)[cols], np.asarray(sw)[cols], group)

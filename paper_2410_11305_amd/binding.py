@@ -21,7 +21,7 @@ EXPORTS = (
     "qspec_gemm_w4a16", "qspec_gemm_w4a4_partials", "qspec_describe_kernel",
     "qspec_accept_workspace_bytes", "qspec_greedy_accept", "qspec_kv_overwrite",
     "qspec_rmsnorm_quant", "qspec_silu_mul_quant", "qspec_hadamard_quant",
-    "qspec_reorder_quant",
+    "qspec_reorder_quant", "qspec_debug_set_plan",
 )
 
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
     L.qspec_hadamard_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     L.qspec_reorder_quant.restype = ci
     L.qspec_reorder_quant.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp]
+    L.qspec_debug_set_plan.restype = ci
+    L.qspec_debug_set_plan.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
     _lib = L
     return L
 
@@ -99,6 +101,12 @@ def packed_weight_bytes(N: int, K: int, group: int = GROUP) -> int:
 
 def workspace_bytes(M: int, N: int, K: int, group: int = GROUP) -> int:
     return lib().qspec_workspace_bytes(M, N, K, group)
+
+
+def debug_set_plan(name: str, value: str = None) -> None:
+    """Force (value) or release (None) one of the library's kernel-plan overrides."""
+    _check(lib().qspec_debug_set_plan(name.encode(), None if value is None else str(value).encode()),
+           "qspec_debug_set_plan")
 
 
 def describe_kernel(w4a4: bool, M: int, N: int, K: int, group: int = GROUP) -> str:

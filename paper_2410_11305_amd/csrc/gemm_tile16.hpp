@@ -98,10 +98,12 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile16w_kernel(TileA
                           (uint32_t)(((lane & 15) ^ (row_in_blk & 15)) << 4);
   const uint32_t x_ustep = (uint32_t)(4 * kWaves) * (uint32_t)p.K * 2u;
   auto dma_x = [&](int q, uint8_t* stage) {
-    const uint32_t gbase = (uint32_t)group_of(q) * 256u + past_end(q);
+    const uint32_t gbase = (uint32_t)group_of(q) * 256u;
+    const uint32_t gone = past_end(q);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const uint32_t off = x_voff + (gbase + (uint32_t)u * x_ustep);
+      // (the marker is OR-ed in last: a sum could carry out of bit 31 for rows near 2 GiB)
+      const uint32_t off = (x_voff + (gbase + (uint32_t)u * x_ustep)) | gone;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(r_act, (lds_ptr_t)(stage + (wave + u * kWaves) * 1024), 16, off, 0, 0, 0);
     }
   };

@@ -39,6 +39,7 @@ inline int check_shape(int M, int N, int K, int group) {
 int check_device() {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return QSPEC_ERR_HIP;
+  (void)hipGetLastError();
   static int verdict[64];   // 0 unknown, 1 ok, 2 unsupported
   if (dev < 0 || dev >= 64) return QSPEC_ERR_UNSUPPORTED;
   if (verdict[dev] == 0) {
@@ -49,6 +50,9 @@ int check_device() {
   return verdict[dev] == 1 ? QSPEC_OK : QSPEC_ERR_UNSUPPORTED;
 }
 
+// QSPEC_ERR_HIP must mean "THIS call's launch failed": check_device(), which every entry
+// point calls after validating its arguments and before launching, drops whatever error an
+// unrelated earlier runtime call left behind; launch_status() then sees only this call's.
 inline int launch_status() { return hipGetLastError() == hipSuccess ? QSPEC_OK : QSPEC_ERR_HIP; }
 
 inline const uint16_t* blob_scales(const void* packed, int N, int K) {
@@ -74,11 +78,64 @@ void launch_w4a16(const GemmArgs& a, hipStream_t s) {
 
 constexpr int kNumCU = 256;
 
-// QSPEC_KERNEL=generic routes M > 32 to the untiled reference kernels (benchmark A/B only)
-bool use_generic() {
-  const char* e = getenv("QSPEC_KERNEL");
-  return e && strcmp(e, "generic") == 0;
+// Plan overrides (benchmark A/B and tests only).  They are parsed ONCE: from the
+// environment at the first use, and afterwards only through qspec_debug_set_plan.  The
+// launch path reads plain integers; no entry point calls getenv.
+//   QSPEC_KERNEL=generic            route M > 32 to the untiled reference kernels
+//   QSPEC_STREAM_W4A4 / _W4A16      "NT,S" or "NT,S,MS": tiles per workgroup, K-slices, token-row blocks
+//   QSPEC_STREAM_MAX_W4A4 / _W4A16  largest M of the streaming kernels without token-row blocks
+//   QSPEC_TILE_W4A4 / _W4A16        "shape,S": workgroup shape index, K-slices
+struct PlanOverrides {
+  bool generic = false;
+  int stream_fields[2] = {0, 0};      // [w4a4]: how many of nt, S, ms were given (0: no override)
+  int stream[2][3] = {{0, 0, 0}, {0, 0, 0}};
+  int stream_max[2] = {0, 0};         // 0: the default bound
+  bool tile_set[2] = {false, false};
+  int tile[2][2] = {{0, 0}, {0, 0}};
+};
+
+// value == nullptr (or unparsable) clears the override named `name`; false: unknown name.
+bool apply_override(PlanOverrides& o, const char* name, const char* value) {
+  if (strcmp(name, "QSPEC_KERNEL") == 0) { o.generic = value && strcmp(value, "generic") == 0; return true; }
+  for (int w4a4 = 0; w4a4 < 2; ++w4a4) {
+    if (strcmp(name, w4a4 ? "QSPEC_STREAM_W4A4" : "QSPEC_STREAM_W4A16") == 0) {
+      int* f = o.stream[w4a4];
+      f[0] = f[1] = 0; f[2] = 1;
+      const int nf = value ? sscanf(value, "%d,%d,%d", &f[0], &f[1], &f[2]) : 0;
+      o.stream_fields[w4a4] = nf >= 2 ? nf : 0;
+      if (nf < 3) f[2] = 1;
+      return true;
+    }
+    if (strcmp(name, w4a4 ? "QSPEC_STREAM_MAX_W4A4" : "QSPEC_STREAM_MAX_W4A16") == 0) {
+      const int v = value ? atoi(value) : 0;
+      // the verify-mode streaming kernel exists for at most two 16-token tiles per workgroup
+      o.stream_max[w4a4] = (v >= 32 && v <= (w4a4 ? 128 : 32)) ? v : 0;
+      return true;
+    }
+    if (strcmp(name, w4a4 ? "QSPEC_TILE_W4A4" : "QSPEC_TILE_W4A16") == 0) {
+      int* f = o.tile[w4a4];
+      o.tile_set[w4a4] = value && sscanf(value, "%d,%d", &f[0], &f[1]) == 2;
+      return true;
+    }
+  }
+  return false;
 }
+
+constexpr const char* kOverrideNames[] = {"QSPEC_KERNEL", "QSPEC_STREAM_W4A4", "QSPEC_STREAM_W4A16",
+                                          "QSPEC_STREAM_MAX_W4A4", "QSPEC_STREAM_MAX_W4A16",
+                                          "QSPEC_TILE_W4A4", "QSPEC_TILE_W4A16"};
+
+PlanOverrides& overrides() {
+  static PlanOverrides o = [] {
+    PlanOverrides init;
+    for (const char* name : kOverrideNames)
+      if (const char* e = getenv(name)) apply_override(init, name, e);
+    return init;
+  }();
+  return o;
+}
+
+bool use_generic() { return overrides().generic; }
 
 // ---------------------------------------------------------------- streaming (small-M) kernel
 constexpr int kStreamMaxM = 32;
@@ -107,14 +164,10 @@ inline int stream_tm_split(int M, int ms) { return stream_tm(16 * (((M + ms - 1)
 
 // Largest M the streaming kernels take without token-row blocks: 32 verify-mode tokens, 64
 // draft-mode tokens (a draft-mode activation operand is a quarter of a verify-mode one).
-// QSPEC_STREAM_MAX_W4A4 / QSPEC_STREAM_MAX_W4A16 override the bound (benchmark A/B only).
+// The QSPEC_STREAM_MAX_* overrides replace the bound (benchmark A/B only).
 int stream_base_max(bool w4a4) {
-  int max_m = w4a4 ? kStreamMaxM4 : kStreamMaxM;
-  if (const char* e = getenv(w4a4 ? "QSPEC_STREAM_MAX_W4A4" : "QSPEC_STREAM_MAX_W4A16")) {
-    const int v = atoi(e);
-    if (v >= 32 && v <= (w4a4 ? 128 : 256)) max_m = v;
-  }
-  return max_m;
+  const int forced = overrides().stream_max[w4a4 ? 1 : 0];
+  return forced ? forced : (w4a4 ? kStreamMaxM4 : kStreamMaxM);
 }
 
 // Up to 128 tokens on layers no larger than 8192 x 8192 the streaming kernel with token-row
@@ -145,13 +198,16 @@ bool plan_wide_stream(bool w4a4, int M, int N, int K, int* nt_out, int* tm_out, 
 
 StreamPlan plan_stream(bool w4a4, int M, int N, int K) {
   const int tiles = N / 16, G = K / kGroup;
-  int nt = 0, S = 0, ms = 1, tm_wide = 0;
-  const char* e = getenv(w4a4 ? "QSPEC_STREAM_W4A4" : "QSPEC_STREAM_W4A16");
-  const int nf = e ? sscanf(e, "%d,%d,%d", &nt, &S, &ms) : 0;
+  const PlanOverrides& ov = overrides();
+  const int nf = ov.stream_fields[w4a4 ? 1 : 0];
+  int nt = ov.stream[w4a4 ? 1 : 0][0], S = ov.stream[w4a4 ? 1 : 0][1], ms = ov.stream[w4a4 ? 1 : 0][2], tm_wide = 0;
   bool forced = nf >= 2 && S >= 1 && S <= G;
   if (nf < 3) ms = 1;
   if (forced && ms > 1) forced = S == 1 && (ms == 2 || ms == 4 || ms == 8);
-  if (forced) forced = stream_nt_ok(nt, stream_tm_split(M, ms)) && (w4a4 || stream_tm_split(M, ms) <= 2);
+  // a forced plan must have an instance and its row blocks must cover all M rows
+  if (forced) forced = stream_nt_ok(nt, stream_tm_split(M, ms)) && (w4a4 || stream_tm_split(M, ms) <= 2) &&
+                       (long long)ms * 16 * stream_tm_split(M, ms) >= M;
+  if (!forced) { nt = 0; S = 0; ms = 1; }
   if (!forced && M > stream_base_max(w4a4)) {
     StreamPlan none{};                                   // nt == 0: no streaming plan, the tiled kernels take it
     if (!plan_wide_stream(w4a4, M, N, K, &nt, &tm_wide, &ms)) return none;
@@ -214,29 +270,40 @@ bool use_stream(bool w4a4, int M, int N, int K) {
   return plan_stream(w4a4, M, N, K).nt > 0;
 }
 
+// Launch the instance <mode, TM, NT> of a streaming plan.  A (TM, NT) pair that is not
+// instantiated (a forced plan can name one) is refused: nothing is launched.
 template <bool W4A4, int TM>
-void launch_stream_tm(const StreamArgs& a, const StreamPlan& plan, hipStream_t s) {
+int launch_stream_tm(const StreamArgs& a, const StreamPlan& plan, hipStream_t s) {
   dim3 grid(plan.blocks * plan.S, plan.ms), block(kStreamWaves * 64);
   switch (plan.nt) {
-    case 1: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 1>), grid, block, 0, s, a); break;
-    case 2: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 2>), grid, block, 0, s, a); break;
-    case 3: if constexpr (TM <= 4) hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 3>), grid, block, 0, s, a); break;
-    case 4: if constexpr (TM <= 4) hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 4>), grid, block, 0, s, a); break;
-    default: if constexpr (TM <= 2) hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 6>), grid, block, 0, s, a); break;
+    case 1: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 1>), grid, block, 0, s, a); return QSPEC_OK;
+    case 2: hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 2>), grid, block, 0, s, a); return QSPEC_OK;
+    case 3:
+      if constexpr (TM <= 4) { hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 3>), grid, block, 0, s, a); return QSPEC_OK; }
+      return QSPEC_ERR_UNSUPPORTED;
+    case 4:
+      if constexpr (TM <= 4) { hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 4>), grid, block, 0, s, a); return QSPEC_OK; }
+      return QSPEC_ERR_UNSUPPORTED;
+    case 6:
+      if constexpr (TM <= 2) { hipLaunchKernelGGL((gemm_stream_kernel<W4A4, TM, 6>), grid, block, 0, s, a); return QSPEC_OK; }
+      return QSPEC_ERR_UNSUPPORTED;
+    default: return QSPEC_ERR_UNSUPPORTED;
   }
 }
 
 template <bool W4A4>
-void launch_stream(StreamArgs a, void* workspace, hipStream_t s) {
+int launch_stream(StreamArgs a, void* workspace, hipStream_t s) {
   const StreamPlan plan = plan_stream(W4A4, a.M, a.N, a.K);
+  if ((long long)plan.ms * 16 * plan.tm < a.M) return QSPEC_ERR_UNSUPPORTED;      // the row blocks must cover M
   a.S = plan.S;
   a.tickets = static_cast<unsigned*>(workspace);
   a.ws = plan.S > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kTicketBytes) : nullptr;
   switch (plan.tm) {
-    case 1: launch_stream_tm<W4A4, 1>(a, plan, s); break;
-    case 2: launch_stream_tm<W4A4, 2>(a, plan, s); break;
-    case 4: if constexpr (W4A4) launch_stream_tm<true, 4>(a, plan, s); break;
-    default: if constexpr (W4A4) launch_stream_tm<true, 8>(a, plan, s); break;
+    case 1: return launch_stream_tm<W4A4, 1>(a, plan, s);
+    case 2: return launch_stream_tm<W4A4, 2>(a, plan, s);
+    case 4: if constexpr (W4A4) return launch_stream_tm<true, 4>(a, plan, s); else return QSPEC_ERR_UNSUPPORTED;
+    case 8: if constexpr (W4A4) return launch_stream_tm<true, 8>(a, plan, s); else return QSPEC_ERR_UNSUPPORTED;
+    default: return QSPEC_ERR_UNSUPPORTED;
   }
 }
 
@@ -273,9 +340,10 @@ inline const TileShape& shape_of(bool w4a4, int i) { return w4a4 ? kShapes4[i] :
 
 // QSPEC_TILE_W4A4 / QSPEC_TILE_W4A16 = "shape,S" override the heuristic (benchmark A/B only).
 bool tile_override(bool w4a4, int* shape, int* S) {
-  const char* e = getenv(w4a4 ? "QSPEC_TILE_W4A4" : "QSPEC_TILE_W4A16");
-  if (!e) return false;
-  if (sscanf(e, "%d,%d", shape, S) != 2) return false;
+  const PlanOverrides& ov = overrides();
+  if (!ov.tile_set[w4a4 ? 1 : 0]) return false;
+  *shape = ov.tile[w4a4 ? 1 : 0][0];
+  *S = ov.tile[w4a4 ? 1 : 0][1];
   return *shape >= 0 && *shape < (w4a4 ? kNumTileShapes : kNumShapes16) && *S >= 1;
 }
 
@@ -419,7 +487,7 @@ const char* qspec_status_string(int status) {
     case QSPEC_ERR_ALIGN: return "pointer not 16-byte aligned";
     case QSPEC_ERR_WORKSPACE: return "workspace too small";
     case QSPEC_ERR_HIP: return "HIP runtime error";
-    case QSPEC_ERR_UNSUPPORTED: return "device is not gfx950";
+    case QSPEC_ERR_UNSUPPORTED: return "device is not gfx950, or a forced plan names a kernel instance that does not exist";
     default: return "unknown status";
   }
 }
@@ -578,7 +646,7 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int 
     StreamArgs st{};
     st.codes = a.codes; st.scalesT = a.scalesT; st.act = qa; st.sa = sa; st.y = a.y;
     st.M = M; st.N = N; st.K = K; st.G = a.G;
-    launch_stream<true>(st, workspace, s);
+    if (int err = launch_stream<true>(st, workspace, s)) return err;
     return launch_status();
   }
   if (!use_generic()) {
@@ -616,7 +684,7 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16, int M, int N, int K,
     StreamArgs st{};
     st.codes = a.codes; st.scalesT = a.scalesT; st.act = x_f16; st.y = a.y;
     st.M = M; st.N = N; st.K = K; st.G = a.G;
-    launch_stream<false>(st, workspace, s);
+    if (int err = launch_stream<false>(st, workspace, s)) return err;
     return launch_status();
   }
   if (!use_generic()) {
@@ -692,6 +760,11 @@ int qspec_kv_overwrite(const void* kv_verify_f16, const int32_t* n_accept, const
   KvArgs a{static_cast<const uint4*>(kv_verify_f16), static_cast<uint4*>(cache_f16), n_accept, pos, gamma, D / 8, S};
   hipLaunchKernelGGL(kv_overwrite_kernel, dim3(B * (gamma + 1)), dim3(256), 0, static_cast<hipStream_t>(stream), a);
   return launch_status();
+}
+
+int qspec_debug_set_plan(const char* name, const char* value) {
+  if (!name) return QSPEC_ERR_NULL;
+  return apply_override(overrides(), name, value) ? QSPEC_OK : QSPEC_ERR_SHAPE;
 }
 
 int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* out, size_t cap) {

@@ -9,7 +9,7 @@ Expected in <in_dir> (see the commands echoed into the summaries):
 The counters are scaled by what they read for the one plain 256 MiB device
 copy that bench.py issues before its timed region (__amd_rocclr_copyBuffer).
 
-usage: python -m paper_2410_11305_amd.profile_summary <in_dir> <out_dir> [tag]
+usage: python profile_summary.py <in_dir> <out_dir> [tag]
 (the digits in the tag name the bench.py --config the runs were made with)
 """
 from __future__ import annotations

@@ -25,3 +25,19 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def plan():
+    """plan(name, value) forces one of the library's kernel-plan overrides through
+    qspec_debug_set_plan; every override set this way is released after the test."""
+    from paper_2410_11305_amd import binding as B
+    used = []
+
+    def force(name, value):
+        B.debug_set_plan(name, value)
+        used.append(name)
+
+    yield force
+    for name in used:
+        B.debug_set_plan(name, None)

@@ -390,6 +390,48 @@ def test_gemm_w4a16_linearity_and_column_locality():
     assert np.array_equal(orc.gemm_w4a16_columns(x, codes, scales, cols), y[:, cols])
 
 
+def test_w4a4_column_helper_is_the_column_slice_of_the_full_product():
+    """gemm_w4a4_columns (the checker of full-size draft-mode outputs) against the columns of
+    gemm_w4a4, itself pinned to exact rationals above: unsorted columns without repeats, a
+    single column, all columns; independently, against a per-element integer/Fraction sum."""
+    from fractions import Fraction
+    M, N, K = 5, 48, 384
+    codes, scales, x = synth.generic_case(36, M, N, K)
+    qa, sa = orc.quant_act(x)
+    y = orc.gemm_w4a4(qa, sa, codes, scales)
+    for cols in (np.array([41, 3, 30, 7, 0, 47]), np.array([17]), np.arange(N)):
+        got = orc.gemm_w4a4_columns(qa, sa, codes, scales, cols)
+        assert got.dtype == np.float16 and got.shape == (M, len(cols))
+        assert np.array_equal(got.view(np.uint16), y[:, cols].view(np.uint16))
+    cols = np.array([41, 3, 30])
+    got = orc.gemm_w4a4_columns(qa, sa, codes, scales, cols)
+    for m in range(M):
+        for c, n in enumerate(cols):
+            acc = Fraction(0)
+            for j in range(K // 128):
+                P = sum(int(qa[m, k]) * int(codes[n, k]) for k in range(128 * j, 128 * j + 128))
+                acc += P * Fraction(float(sa[m, j])) * Fraction(float(scales[n, j]))
+            assert got[m, c] == np.float16(float(acc)) or abs(float(got[m, c]) - float(acc)) <= 2.0 ** -11 * abs(float(acc))
+
+
+def test_planted_mistakes_in_the_column_helpers_fail_their_pin(monkeypatch):
+    """A column helper that slices only the codes (scales of the first columns), or that
+    sorts its columns, is caught."""
+    def scales_not_sliced(qa, sa, qw, sw, cols, group=128):
+        cols = np.asarray(cols)
+        return orc.gemm_w4a4(qa, sa, np.asarray(qw)[cols], np.asarray(sw)[:len(cols)], group)
+
+    def sorted_columns(qa, sa, qw, sw, cols, group=128):
+        cols = np.sort(np.asarray(cols))
+        return orc.gemm_w4a4(qa, sa, np.asarray(qw)[cols], np.asarray(sw)[cols], group)
+
+    for mutant in (scales_not_sliced, sorted_columns):
+        with monkeypatch.context() as mp:
+            mp.setattr(orc, "gemm_w4a4_columns", mutant)
+            with pytest.raises(AssertionError):
+                test_w4a4_column_helper_is_the_column_slice_of_the_full_product()
+
+
 def test_fp16_weight_rounding_variant_is_close_but_distinct():
     M, N, K = 8, 64, 1024
     codes, scales, x = synth.generic_case(34, M, N, K)
