@@ -201,6 +201,25 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16,
                      void* y_f16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * qspec_gemm_w4a16 for callers that cannot allocate device memory and have no
+ * workspace to pass: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, result and kernels as qspec_gemm_w4a16, but the
+ * K-slice scratch (arrival counters and partial sums) is a fixed array inside the
+ * library's device image, 32 MiB + 16 KiB per GPU, held by every
+ * GPU the library runs on until the process ends.  The call allocates nothing.
+ *   - A shape whose plan needs more than that returns QSPEC_ERR_WORKSPACE and launches
+ *     nothing (qspec_workspace_bytes tells: use qspec_gemm_w4a16 with a workspace).
+ *   - Every call on one GPU shares that GPU's array; the counters are cleared by a small
+ *     kernel in front of the GEMM.  Calls that may overlap on one GPU (different
+ *     streams) race: serialise them, or give all but one a workspace of their own.
+ *   - The first call on a device looks up the array's device address
+ *     (hipGetSymbolAddress); make that first call outside graph capture.
+ */
+int qspec_gemm_w4a16_noalloc(const void* packed, const void* x_f16,
+                             int M, int N, int K, int group,
+                             void* y_f16, void* stream);
+
+/*
  * Debug entry: the exact per-group integer partial sums of the draft product
  * for output columns n0 .. n0+n_count-1 (n0 and n_count multiples of 16):
  *   partials[m, n - n0, j] = P[m,n,j], int32 [M, n_count, G] row-major.

@@ -22,6 +22,7 @@ EXPORTS = (
     "qspec_accept_workspace_bytes", "qspec_greedy_accept", "qspec_kv_overwrite",
     "qspec_rmsnorm_quant", "qspec_silu_mul_quant", "qspec_hadamard_quant",
     "qspec_reorder_quant", "qspec_debug_set_plan",
+    "qspec_gemm_w4a16_noalloc",
 )
 
 
@@ -81,6 +82,8 @@ def lib() -> ctypes.CDLL:
     L.qspec_hadamard_quant.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
     L.qspec_reorder_quant.restype = ci
     L.qspec_reorder_quant.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp]
+    L.qspec_gemm_w4a16_noalloc.restype = ci
+    L.qspec_gemm_w4a16_noalloc.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
     L.qspec_debug_set_plan.restype = ci
     L.qspec_debug_set_plan.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
     _lib = L
@@ -276,6 +279,20 @@ def gemm_w4a16(packed: torch.Tensor, x: torch.Tensor, N: int, y: torch.Tensor = 
     _check(lib().qspec_gemm_w4a16(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"),
                                   M, N, K, group, _dev(y, torch.float16, "y"), ws, ws_bytes, _stream()),
            "qspec_gemm_w4a16")
+    return y
+
+
+NOALLOC_SCRATCH_BYTES = (32 << 20) + 16384
+
+
+def gemm_w4a16_noalloc(packed: torch.Tensor, x: torch.Tensor, N: int, y: torch.Tensor,
+                       group: int = GROUP) -> torch.Tensor:
+    """qspec_gemm_w4a16 on the library's built-in scratch: the caller passes every buffer,
+    nothing is allocated here or in the library."""
+    M, K = x.shape
+    _check(lib().qspec_gemm_w4a16_noalloc(_dev(packed, torch.uint8, "packed"), _dev(x, torch.float16, "x"),
+                                          M, N, K, group, _dev(y, torch.float16, "y"), _stream()),
+           "qspec_gemm_w4a16_noalloc")
     return y
 
 

@@ -20,6 +20,14 @@
 
 using namespace qspec;
 
+// Scratch of qspec_gemm_w4a16_noalloc: arrival counters (first kTicketBytes) and K-slice
+// partial sums, for callers that can neither allocate nor pass a workspace.  Every GPU
+// the library runs on holds its own copy until the process ends.  In host code this name
+// is only a handle for hipGetSymbolAddress; kernels and fills take the address that call
+// returned for the current device (scratch_of_device below), never the name.
+constexpr size_t kScratchBytes = ((size_t)32 << 20) + 16384;   // 32 MiB of partial sums + 16 KiB of counters
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -467,6 +475,35 @@ ArgmaxPlan plan_argmax(int V) {
   return ArgmaxPlan{C, chunk};
 }
 
+// Device address of `scratch` on the current device, looked up once per device (with that
+// device current) and kept.  nullptr: the lookup failed.
+constexpr int kMaxDevices = 64;
+void* scratch_of_device(int* status) {
+  static void* ptr[kMaxDevices];
+  static bool known[kMaxDevices];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { *status = QSPEC_ERR_HIP; return nullptr; }
+  if (!known[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      *status = QSPEC_ERR_HIP;
+      return nullptr;
+    }
+    ptr[dev] = p;
+    known[dev] = true;
+  }
+  *status = QSPEC_OK;
+  return ptr[dev];
+}
+
+// Zero the arrival counters at the head of a scratch area (a kernel, not a memset: the
+// launch may be captured into a graph).
+__global__ __launch_bounds__(256) void clear_tickets_kernel(unsigned* tickets, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) tickets[i] = 0u;
+}
+
 inline bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
 
 inline int check_accept_shape(int B, int gamma, int V) {
@@ -701,6 +738,25 @@ int qspec_gemm_w4a16(const void* packed, const void* x_f16, int M, int N, int K,
     default: launch_w4a16<8>(a, s); break;
   }
   return launch_status();
+}
+
+int qspec_gemm_w4a16_noalloc(const void* packed, const void* x_f16, int M, int N, int K, int group,
+                             void* y_f16, void* stream) {
+  if (!packed || !x_f16 || !y_f16) return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, N, K, group)) return st;
+  if (misaligned(packed) || misaligned(x_f16) || misaligned(y_f16)) return QSPEC_ERR_ALIGN;
+  const size_t need = qspec_workspace_bytes(M, N, K, group);
+  if (need > kScratchBytes) return QSPEC_ERR_WORKSPACE;       // beyond the built-in scratch: use qspec_gemm_w4a16
+  if (int st = check_device()) return st;
+  int st = QSPEC_OK;
+  void* ws = scratch_of_device(&st);
+  if (!ws) return st;
+  if (need > 0) {
+    // the counters must start at zero whatever an earlier (possibly failed) call left
+    hipLaunchKernelGGL(clear_tickets_kernel, dim3(kMaxTickets / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<unsigned*>(ws), kMaxTickets);
+  }
+  return qspec_gemm_w4a16(packed, x_f16, M, N, K, group, y_f16, ws, kScratchBytes, stream);
 }
 
 int qspec_gemm_w4a4_partials(const void* packed, const uint8_t* qa, int M, int N, int K, int group,
