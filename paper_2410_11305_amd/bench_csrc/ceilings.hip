@@ -1,0 +1,188 @@
+// Ceiling microbenchmarks for bench.py (NOT part of libqspec.so or of its ABI): what
+// the machine itself sustains on the two resources the GEMM kernels are bound by, in
+// the launch geometry those kernels use.  bench.py times them beside the kernels and
+// prints the figures in its "ceilings" object.
+//   ceil_stream_read   bare streaming read of `bytes` bytes: workgroups of 8 wavefronts,
+//                      a wavefront pulls 1 KB per load instruction (16 B per lane, the
+//                      streaming-load hint), two loads in flight per register set, two
+//                      sets alternating: the memory side of gemm_stream_kernel with the
+//                      arithmetic, the activations and the output removed.
+//   ceil_mfma          matrix-unit loop without memory traffic in the loop: operands are
+//                      loaded once from `operands` (random data: the clock the part holds
+//                      depends on how many bits toggle) and re-used; kind 0:
+//                      v_mfma_f32_32x32x16_f16, kind 1: v_mfma_i32_32x32x32_i8, kind 2:
+//                      the int8 loop with the draft mode's per-group rescaling attached
+//                      (two fp32 fused multiply-adds per output and group of 128, the
+//                      least that y += float(P) * sa * sw takes), which is what bounds
+//                      the draft mode at large M whatever the kernel does around it.
+//   ceil_empty         an empty kernel (launch + drain cost inside a captured graph).
+// All pointers are device pointers; work is enqueued on `stream`; 0 = ok.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+__device__ inline rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+
+constexpr int kWaves = 8;
+
+// Workgroup b reads tiles [b*per, (b+1)*per) of 1 KB; wave w takes tiles w, w+8, ...
+__global__ __launch_bounds__(kWaves * 64) void stream_read_kernel(const uint8_t* buf, uint32_t tiles, uint32_t per,
+                                                                 uint32_t* sink) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t t0 = blockIdx.x * per, t1 = min(tiles, t0 + per);
+  const rsrc_t r = make_rsrc(buf, tiles * 1024u);
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  uint32_t t = t0 + wave;
+  auto ld = [&](uint32_t tile) -> u32x4 {
+    const uint32_t off = tile < t1 ? tile * 1024u + lane * 16u : 0x80000000u;    // out of range: zeros, no traffic
+    return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 2);
+  };
+  u32x4 a0 = ld(t), a1 = ld(t + kWaves);
+  for (; t < t1; t += 4 * kWaves) {
+    const u32x4 b0 = ld(t + 2 * kWaves), b1 = ld(t + 3 * kWaves);
+    __builtin_amdgcn_sched_barrier(0);
+    acc ^= a0; acc ^= a1;
+    __builtin_amdgcn_sched_barrier(0);
+    a0 = ld(t + 4 * kWaves); a1 = ld(t + 5 * kWaves);
+    __builtin_amdgcn_sched_barrier(0);
+    acc ^= b0; acc ^= b1;
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  const uint32_t v = acc.x ^ acc.y ^ acc.z ^ acc.w;
+  if (v == 0x9E3779B9u) sink[0] = v;          // practically never: keeps the loads alive
+}
+
+template <int KIND>
+__global__ __launch_bounds__(512, 1) void mfma_loop_kernel(const uint4* operands, int iters, float* out) {
+  // four independent accumulator tiles per wave so that the matrix unit never waits on a
+  // dependent accumulation; two waves per SIMD (512 threads, one workgroup per compute unit)
+  const int tid = blockIdx.x * 512 + threadIdx.x;
+  uint4 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = operands[(size_t)(tid * 8 + i) & 0xFFFFF];
+    b[i] = operands[(size_t)(tid * 8 + 4 + i) & 0xFFFFF];
+  }
+  if (KIND == 0) {
+    v16f c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) c[i][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          c[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a[j]), __builtin_bit_cast(v8h, b[(i + j) & 3]), c[i], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += c[i][r];
+    if (s == 12345.678f) out[0] = s;
+  } else if (KIND == 1) {
+    v16i c[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) c[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          c[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(v4i, a[j]), __builtin_bit_cast(v4i, b[(i + j) & 3]), c[i], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += c[i][r];
+    if (s == 0x12345678) out[0] = (float)s;
+  } else {
+    // one "tile-group" = 4 MFMAs (128 k) into a fresh int32 tile, then two fp32 FMAs per
+    // output: t = fma(P, sw, c0); acc = fma(t, sa, acc).  Two tiles alternate so that the
+    // MFMAs of one overlap the scaling of the other, as a kernel would arrange it.
+    float acc[2][16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    const float sw = __builtin_bit_cast(float, a[0].x & 0x3FFFFFFFu), sa = __builtin_bit_cast(float, b[0].x & 0x3FFFFFFFu);
+    v16i P[2], seed;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { P[0][r] = 0; P[1][r] = 0; seed[r] = 0x4B400000; }
+    asm volatile("" : "+v"(seed));                   // a register set of its own: never rebuilt in the loop
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {                  // 4 tile-groups per iteration = 16 MFMAs, like the plain loops
+        v16i c;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          c = __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(v4i, a[j]), __builtin_bit_cast(v4i, b[(i + j) & 3]), j == 0 ? seed : c, 0, 0, 0);
+          // the scaling of the tile finished before this one, a quarter per MFMA
+#pragma unroll
+          for (int r = 4 * j; r < 4 * j + 4; ++r) {
+            const int bits = P[(i + 1) & 1][r];
+            acc[i & 1][r] = __builtin_fmaf(__builtin_fmaf(__builtin_bit_cast(float, bits), sw, -sw), sa, acc[i & 1][r]);
+          }
+        }
+        P[i & 1] = c;
+      }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (s == 12345.678f) out[0] = s;
+  }
+}
+
+__global__ void empty_kernel() {}
+
+}  // namespace
+
+extern "C" {
+
+int ceil_stream_read(const void* buf, size_t bytes, int tiles_per_block, void* sink, void* stream) {
+  if (!buf || !sink || bytes < 1024 || bytes >= 0x7fffffffULL || tiles_per_block < 1) return 1;
+  const uint32_t tiles = (uint32_t)(bytes / 1024);
+  const uint32_t blocks = (tiles + tiles_per_block - 1) / tiles_per_block;
+  hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(kWaves * 64), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint8_t*>(buf), tiles, (uint32_t)tiles_per_block, static_cast<uint32_t*>(sink));
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+// operands: at least 16 MiB of device memory (2^20 uint4); blocks workgroups of 512 threads;
+// every wavefront issues iters * 16 matrix instructions.
+int ceil_mfma(int kind, const void* operands, int blocks, int iters, void* out, void* stream) {
+  if (!operands || !out || blocks < 1 || iters < 1) return 1;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const uint4* op = static_cast<const uint4*>(operands);
+  float* o = static_cast<float*>(out);
+  if (kind == 0) hipLaunchKernelGGL(mfma_loop_kernel<0>, dim3(blocks), dim3(512), 0, s, op, iters, o);
+  else if (kind == 1) hipLaunchKernelGGL(mfma_loop_kernel<1>, dim3(blocks), dim3(512), 0, s, op, iters, o);
+  else if (kind == 2) hipLaunchKernelGGL(mfma_loop_kernel<2>, dim3(blocks), dim3(512), 0, s, op, iters, o);
+  else return 1;
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+int ceil_empty(void* stream) {
+  hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+}  // extern "C"

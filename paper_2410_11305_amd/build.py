@@ -10,6 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libqspec.so")
 SOURCES = [os.path.join(HERE, "csrc", "qspec_api.hip")]
+# bench-only microbenchmarks (machine ceilings); a library of its own, not part of the ABI
+CEIL_LIB_PATH = os.path.join(HERE, "libqspec_ceilings.so")
+CEIL_SOURCES = [os.path.join(HERE, "bench_csrc", "ceilings.hip")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
@@ -66,6 +69,12 @@ def build(verbose: bool = True) -> str:
     spilled = spilling_kernels(res.stdout, NO_SPILL_KERNELS)
     if spilled:
         raise RuntimeError("kernels that must not spill registers do: " + ", ".join(spilled))
+    cmd = [hipcc(), *HIPCC_FLAGS, "-o", CEIL_LIB_PATH, *CEIL_SOURCES]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
     return LIB_PATH
 
 

@@ -93,23 +93,23 @@ def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
         lines.append(f"  {k:68s} {fetch[k][0]:6d} {fb/1e6:10.2f} {wb/1e6:10.2f} {(fb+wb)/1e6:10.2f}")
     with open(os.path.join(out_dir, f"{tag}_hbm_counters.txt"), "w") as f:
         f.write("\n".join(lines) + "\n")
-    # one table for bench.py, merged over the workloads summarised so far (kernel
-    # symbols differ between workloads; a repeated symbol takes the newest figure)
+    # one table for bench.py, keyed by configuration and then by kernel symbol (the same
+    # symbol moves different byte counts in different configurations)
     path = os.path.join(out_dir, "hbm_traffic.json")
-    merged, sources = {}, []
+    by_config, sources = {}, []
     try:
         with open(path) as f:
             old = json.load(f)
-        merged, sources = old.get("bytes_per_launch", {}), old.get("sources", [])
+        by_config, sources = old.get("by_config", {}), old.get("sources", [])
     except (OSError, ValueError):
         pass
-    merged.update(per_launch)
+    by_config[cfg] = per_launch
     src = f"{tag}_hbm_counters.txt"
     if src not in sources:
         sources.append(src)
     with open(path, "w") as f:
         json.dump({"sources": sources, "fetch_scale": round(f_scale, 4),
-                   "write_scale": round(w_scale, 4), "bytes_per_launch": merged}, f, indent=1)
+                   "write_scale": round(w_scale, 4), "by_config": by_config}, f, indent=1)
         f.write("\n")
 
 
