@@ -1,4 +1,4 @@
-// Tiled draft-mode (W4A4) kernel for M > 32 on v_mfma_i32_32x32x32_i8 (paper
+// Tiled draft-mode (W4A4) kernel for M > 64 on v_mfma_i32_32x32x32_i8 (paper
 // Sec. 1 item (2): both operands stay 4-bit integers on the low-precision matrix
 // units; Sec. 4.1: groups of 128).
 //
@@ -6,9 +6,24 @@
 // tile P (exact), then  acc += float(P) * (sa[m,g] * 2^-8) * sw[n,g]  in fp32.
 // Both int8 operands are 16*code (a nibble moved to the high half of a byte), so
 // P is 256 times the true partial sum and 2^-8 rides on the activation scale.
-// That epilogue is 3 VALU operations per output and group against 1/4 MFMA: the
-// kernel is bound by vector arithmetic, not by the matrix unit, and the schedule
-// below exists to keep the MFMAs and the LDS traffic hidden under it.
+// With g = 128 that rescaling, not the matrix unit, bounds the kernel (one fp32
+// operation per output and group costs as many cycles as the MFMAs of that
+// group), so the kernel is built around doing it in TWO vector instructions per
+// output and group and nothing else per output:
+//   - MFMA roles: A = activations, B = weights.  A lane's 16 accumulator registers
+//     are then 16 tokens of ONE output feature, so the weight scale is one value
+//     per lane and group (one conversion, one multiply) instead of sixteen.
+//   - The int32 -> fp32 conversion is folded away: the MFMA chain of a tile starts
+//     from a register set holding the bit pattern of 1.5 * 2^23, so the finished
+//     register READ AS A FLOAT is 12582912 + 256 P exactly (|256 P| <= 2^21), and
+//     t = fma(that, sw, -12582912 * sw) is the correctly rounded 256 P * sw (the
+//     constant is exact: sw has 11 significant bits, 1.5 * 2^23 two).
+//   - acc = fma(t, sa[token], acc): the sixteen token scales of a tile sit in ONE
+//     register (lane i of each row of 16 lanes holds the scale of the token that
+//     accumulator register i belongs to) and reach the multiply through the DPP
+//     row-broadcast operand of v_fmac_f32: no register per token, no move.
+//   - The rescaling of a tile runs under the MFMAs of the next tile, the one of a
+//     group's last tile under the first MFMAs of the next group.
 //
 // A workgroup of WGN x WGM wavefronts owns BN x BM outputs (BN = 32*PN*WGN,
 // BM = 32*PM*WGM) over a range of K groups.
@@ -16,27 +31,64 @@
 //     -> registers two groups ahead, are widened to int8 once per workgroup and
 //     written to one of three LDS stages at the end of a group; one barrier per
 //     group.  Row layout: 8 slots of 16 bytes (slot kb: low nibbles of k-block kb,
-//     slot 4+kb: high nibbles), slot index xor-ed with (row/2)%8 so that 16
-//     consecutive rows at one slot hit 16 different bank groups.
+//     slot 4+kb: high nibbles), slot index xor-ed with act_swizzle(row) so that the
+//     operand reads and the staging writes are free of bank conflicts.
 //   - Weights and their scales: straight into registers in MFMA operand layout
 //     through a ring of three groups (slots named statically: the group loop is
 //     unrolled three times, which also fixes the LDS stage of a group).
 //
-// A operand (32 rows x 32 k): lane l = (h = l / 32, row = l % 32) supplies 16 k of
-// its row.  It fetches the 16 bytes of blob tile lane (row % 16, kb = h) ["lo"] and
-// (row % 16, kb = h + 2) ["hi"] of the 16-row tile holding its row; each gives two
-// operands (low nibbles, high nibbles), four MFMA steps in all.  The B operand of
-// a step is, for lane (h, m = l % 32), the matching slot of token row m: kb = h or
-// h + 2, low or high nibbles.  Any assignment of k to steps and lanes is valid as
-// long as both operands use the same one: a group's dot product is order-free.
-// D: lane holds column m = l % 32 and rows 8a + 4h + r (a, r = 0..3) in register
-// 4a + r.
+// B operand (32 k x 32 features): lane l = (h = l / 32, col = l % 32) supplies 16 k
+// of its weight row.  It fetches the 16 bytes of blob tile lane (col % 16, kb = h)
+// ["lo"] and (col % 16, kb = h + 2) ["hi"] of the 16-row tile holding its row; each
+// gives two operands (low nibbles, high nibbles), four MFMA steps in all.  The A
+// operand of a step is, for lane (h, m = l % 32), the matching slot of token row m:
+// kb = h or h + 2, low or high nibbles.  Any assignment of k to steps and lanes is
+// valid as long as both operands use the same one: a group's dot product is
+// order-free.  D: lane holds output feature n = l % 32 and tokens 8a + 4h + r
+// (a, r = 0..3) in register 4a + r.
 #pragma once
 #include "gemm_tile16.hpp"
 
 namespace qspec {
 
 typedef int v16i __attribute__((ext_vector_type(16)));
+
+// acc += S[lane R of this lane's row of 16] * t  in one instruction: v_fmac_f32 whose
+// first operand comes through the DPP row broadcast.  (The compiler does not fold a DPP
+// move into the multiply-add by itself; written out, it is one VALU operation.)  S must
+// not have been written by a vector ALU instruction in the two instructions before.
+template <int R>
+__device__ __forceinline__ void fmac_row_bcast(float& acc, float S, float t) {
+  asm volatile("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "+v"(acc) : "v"(S), "v"(t), "n"(R));
+}
+__device__ __forceinline__ void fmac_row_bcast_r(float& acc, float S, float t, int r) {   // r is a constant after unrolling
+  switch (r) {
+    case 0: fmac_row_bcast<0>(acc, S, t); break;
+    case 1: fmac_row_bcast<1>(acc, S, t); break;
+    case 2: fmac_row_bcast<2>(acc, S, t); break;
+    case 3: fmac_row_bcast<3>(acc, S, t); break;
+    case 4: fmac_row_bcast<4>(acc, S, t); break;
+    case 5: fmac_row_bcast<5>(acc, S, t); break;
+    case 6: fmac_row_bcast<6>(acc, S, t); break;
+    case 7: fmac_row_bcast<7>(acc, S, t); break;
+    case 8: fmac_row_bcast<8>(acc, S, t); break;
+    case 9: fmac_row_bcast<9>(acc, S, t); break;
+    case 10: fmac_row_bcast<10>(acc, S, t); break;
+    case 11: fmac_row_bcast<11>(acc, S, t); break;
+    case 12: fmac_row_bcast<12>(acc, S, t); break;
+    case 13: fmac_row_bcast<13>(acc, S, t); break;
+    case 14: fmac_row_bcast<14>(acc, S, t); break;
+    default: fmac_row_bcast<15>(acc, S, t); break;
+  }
+}
+
+// LDS slot swizzle of an activation row (8 slots of 16 bytes in a 128-byte row): slot s of
+// row r is stored at slot s ^ act_swizzle(r).  Chosen so that a 16-byte access per lane is
+// free of bank conflicts whether the LDS serves 8 lanes (128 B) or 16 lanes (256 B) per
+// clock: 8 consecutive rows at one slot land in 8 different slots, and among 16
+// consecutive rows the 8 of equal parity (which share the same half of a 256-byte window)
+// do as well.
+__device__ __forceinline__ int act_swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 template <int PN, int PM, int WGN, int WGM, int OCC>
 __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileArgs p) {
@@ -48,15 +100,17 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
   constexpr int kStageBytes = kActBytes + BM * 4;    // + sa[m] * 2^-8 of the group
   constexpr int kChunks = BM * 4;                    // 16-byte pieces of codes per group
   constexpr int U = (kChunks + kThreads - 1) / kThreads;
+  constexpr int kTiles = PN * PM;
   static_assert(kChunks % kThreads == 0 || kChunks < kThreads, "whole passes, or one partial pass");
   static_assert(BM <= kThreads, "one thread per token row stages the activation scale");
+  static_assert(kTiles % 2 == 0, "the last tile of a group and the first of the next use different int32 tiles");
   __shared__ __attribute__((aligned(16))) uint8_t lds[NW * kStageBytes];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wn = wave % WGN, wm = wave / WGN;
-  const int m32 = lane & 31, h = lane >> 5;
+  const int l32 = lane & 31, h = lane >> 5;
   const int G = p.G;
   const TileCoord tc = tile_coord(p);
   const int g0 = tc.g0, g1 = tc.g1;
@@ -98,35 +152,34 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
       const int row = idx >> 2, c = idx & 3;
       if (kChunks % kThreads == 0 || idx < kChunks) {
         const I8Pair q = unpack_i8(xs[u]);
-        const int sw = (row >> 1) & 7;
-        *reinterpret_cast<v4i*>(base + row * 128 + ((c ^ sw) << 4)) = q.lo;
-        *reinterpret_cast<v4i*>(base + row * 128 + (((c + 4) ^ sw) << 4)) = q.hi;
+        const int sw = act_swizzle(row);
+        // Four lanes write one row.  Rows whose bits 0 and 1 differ write their high-nibble
+        // half first: the lanes that share a clock (two or four rows) then never meet in a bank.
+        const bool hi_first = ((row ^ (row >> 1)) & 1) != 0;
+        const int s0 = hi_first ? c + 4 : c, s1 = hi_first ? c : c + 4;
+        *reinterpret_cast<v4i*>(base + row * 128 + ((s0 ^ sw) << 4)) = hi_first ? q.hi : q.lo;
+        *reinterpret_cast<v4i*>(base + row * 128 + ((s1 ^ sw) << 4)) = hi_first ? q.lo : q.hi;
       }
     }
     if (tid < BM) *reinterpret_cast<float*>(base + kActBytes + tid * 4) = sas * 0.00390625f;   // 2^-8, exact
   };
 
-  // ---- weights: ring of NW groups; per 32-row pair two 16-byte pieces and the
-  // scales of the four runs of rows this lane's D registers cover
+  // ---- weights: ring of NW groups; per 32-row pair two 16-byte pieces and the scale
+  // of this lane's row
   uint4 wlo[NW][PN], whi[NW][PN];
-  uint2 sq[NW][PN][4];
-  const int n_lane = n0 + m32;          // this lane's weight row in pair 0
+  uint32_t sq[NW][PN];
+  const int n_lane = n0 + l32;          // this lane's weight row in pair 0
   const uint32_t w_voff = (uint32_t)(n_lane >> 4) * G * 1024u + (uint32_t)((n_lane & 15) + 16 * h) * 16u;
   auto load_w = [&](int d, int q) {
     const uint32_t gone = past_end(q);
     const int g = g0 + q;
 #pragma unroll
     for (int j = 0; j < PN; ++j) {
-      const uint32_t none = (uint32_t)((p.N - 1 - (n_lane + 32 * j)) >> 31) << 31;
+      const uint32_t skip = gone | ((uint32_t)((p.N - 1 - (n_lane + 32 * j)) >> 31) << 31);
       const uint32_t wo = w_voff + (uint32_t)(2 * j) * G * 1024u + (uint32_t)g * 1024u;
-      wlo[d][j] = buf_load16(r_codes, wo | gone | none);
-      whi[d][j] = buf_load16(r_codes, (wo + 512u) | gone | none);
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const int n = n0 + 32 * j + 8 * a + 4 * h;
-        const uint32_t nonea = (uint32_t)((p.N - 1 - n) >> 31) << 31;
-        sq[d][j][a] = buf_load8(r_scales, (((uint32_t)g * (uint32_t)p.N + (uint32_t)n) * 2u) | gone | nonea);
-      }
+      wlo[d][j] = buf_load16(r_codes, wo | skip);
+      whi[d][j] = buf_load16(r_codes, (wo + 512u) | skip);
+      sq[d][j] = buf_load_u16(r_scales, (((uint32_t)g * (uint32_t)p.N + (uint32_t)(n_lane + 32 * j)) * 2u) | skip);
     }
   };
 
@@ -138,6 +191,29 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][t][r] = 0.0f;
 
+  // the start value of every int32 tile (see the head of this file), in a register set of
+  // its own that the loop never rebuilds
+  constexpr int kSeedBits = 0x4B400000;                // 12582912.0f = 1.5 * 2^23
+  v16i seed;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) seed[r] = kSeedBits;
+  asm volatile("" : "+v"(seed));
+  v16i P[2];                                           // int32 tiles, alternating
+  P[0] = seed;
+  P[1] = seed;
+  // the rescaling still owed to the last tile of the group before (none yet: zeros)
+  float pend_sw = 0.0f, pend_swc = 0.0f, pend_S = 0.0f;
+
+  // t = 256 P sw (correctly rounded), acc += (sa 2^-8) t, for registers 4*part .. 4*part+3
+  auto rescale_quarter = [&](const v16i& Pt, float sw, float swc, float S, float (&a)[16], int part) __attribute__((always_inline)) {
+#pragma unroll
+    for (int r = 4 * part; r < 4 * part + 4; ++r) {
+      const int bits = Pt[r];                          // (a copy: bit_cast of a vector element lvalue reads element 0)
+      const float t = __builtin_fmaf(__builtin_bit_cast(float, bits), sw, swc);
+      fmac_row_bcast_r(a[r], S, t, r);
+    }
+  };
+
   // prologue: groups 0 and 1 into stages 0 and 1, the ring filled
   load_x(0);
   store_x(0);
@@ -147,107 +223,92 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
   store_x(1);
   __syncthreads();
 
+  // this lane's entry of a token tile's scale register: lane i of a row of 16 holds the
+  // scale of the token that accumulator register i belongs to (8 (i/4) + 4 h + i % 4)
+  const int s_row = 8 * ((lane & 15) >> 2) + 4 * h + (lane & 3);
+
   auto group_body = [&](auto slot_c, int q) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_c)::value;
     const uint8_t* xl = lds + SLOT * kStageBytes;
     load_x(q + 2);                               // lands in stage (SLOT + 2) % 3 at the end of this group
     __builtin_amdgcn_sched_barrier(0);
 
-    // operands of this group: four A operands per 32-row pair, fp32 weight scales
-    v4i a[PN][4];
-    float swf[PN][16];
+    // operands of this group: four B operands per 32-row pair, the lane's weight scale
+    v4i b[PN][4];
+    float swf[PN], swc[PN];
 #pragma unroll
     for (int j = 0; j < PN; ++j) {
       const I8Pair lo = unpack_i8(wlo[SLOT][j]), hi = unpack_i8(whi[SLOT][j]);
-      a[j][0] = lo.lo; a[j][1] = lo.hi; a[j][2] = hi.lo; a[j][3] = hi.hi;
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        swf[j][4 * q4 + 0] = half_bits_to_float((uint16_t)(sq[SLOT][j][q4].x & 0xFFFF));
-        swf[j][4 * q4 + 1] = half_bits_to_float((uint16_t)(sq[SLOT][j][q4].x >> 16));
-        swf[j][4 * q4 + 2] = half_bits_to_float((uint16_t)(sq[SLOT][j][q4].y & 0xFFFF));
-        swf[j][4 * q4 + 3] = half_bits_to_float((uint16_t)(sq[SLOT][j][q4].y >> 16));
-      }
+      b[j][0] = lo.lo; b[j][1] = lo.hi; b[j][2] = hi.lo; b[j][3] = hi.hi;
+      swf[j] = half_bits_to_float((uint16_t)sq[SLOT][j]);
+      swc[j] = swf[j] * -12582912.0f;            // exact: 11 significant bits times 1.5 * 2^23
     }
-    load_w(SLOT, q + NW);                        // the slot's contents are in a[] and swf[] now
+    load_w(SLOT, q + NW);                        // the slot's contents are in b[] and swf[] now
     __builtin_amdgcn_sched_barrier(0);
 
-    v4i b[2][4];                                 // B operands of token tile t live in b[t & 1]
-    float sam[2];
-    auto read_tile = [&](int t, int buf) {
-      const int row = mw0 + 32 * t + m32;
-      const int sw = (row >> 1) & 7;
-      b[buf][0] = *reinterpret_cast<const v4i*>(xl + row * 128 + ((h ^ sw) << 4));
-      b[buf][1] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 4) ^ sw) << 4));
-      b[buf][2] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 2) ^ sw) << 4));
-      b[buf][3] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 6) ^ sw) << 4));
-      sam[buf] = *reinterpret_cast<const float*>(xl + kActBytes + row * 4);
+    v4i a[2][4];                                 // A operands of token tile t live in a[t & 1]
+    float S[2];                                  // its sixteen token scales (see s_row)
+    auto read_operands = [&](int t, int buf) {
+      const int row = mw0 + 32 * t + l32;
+      const int sw = act_swizzle(row);
+      a[buf][0] = *reinterpret_cast<const v4i*>(xl + row * 128 + ((h ^ sw) << 4));
+      a[buf][1] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 4) ^ sw) << 4));
+      a[buf][2] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 2) ^ sw) << 4));
+      a[buf][3] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 6) ^ sw) << 4));
     };
-    v16i P[2];                                   // int32 tiles, alternating
-    // scale-and-add of the tile finished one step ago, a quarter at a time
-    auto epilogue_quarter = [&](int idx, int part) {
-      const int t = idx / PN, j = idx % PN;
-#pragma unroll
-      for (int r = 4 * part; r < 4 * part + 4; ++r)
-        acc[j][t][r] += (float)P[idx & 1][r] * (sam[t & 1] * swf[j][r]);
-      // Pin the arithmetic here: nothing else uses these sums before the end of the
-      // kernel, and instruction selection would otherwise park the whole epilogue of
-      // every group at the bottom of the unrolled loop body (with every int32 tile
-      // kept alive until then).
-      asm volatile("" : "+v"(acc[j][t][4 * part]), "+v"(acc[j][t][4 * part + 1]), "+v"(acc[j][t][4 * part + 2]),
-                        "+v"(acc[j][t][4 * part + 3]));
+    auto read_scales = [&](int t, int buf) {
+      S[buf] = *reinterpret_cast<const float*>(xl + kActBytes + (mw0 + 32 * t + s_row) * 4);
     };
-    read_tile(0, 0);
+    read_operands(0, 0);
+    read_scales(0, 0);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int idx = 0; idx < PN * PM; ++idx) {
+    for (int idx = 0; idx < kTiles; ++idx) {
       const int t = idx / PN, j = idx % PN;
       if (j == 0 && t + 1 < PM) {
-        // operands of the next token tile, a whole tile ahead of their MFMAs (its
-        // scale is fetched further down, once its register is free)
-        const int row = mw0 + 32 * (t + 1) + m32;
-        const int sw = (row >> 1) & 7;
-        const int buf = (t + 1) & 1;
-        b[buf][0] = *reinterpret_cast<const v4i*>(xl + row * 128 + ((h ^ sw) << 4));
-        b[buf][1] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 4) ^ sw) << 4));
-        b[buf][2] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 2) ^ sw) << 4));
-        b[buf][3] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 6) ^ sw) << 4));
+        // operands of the next token tile, a whole tile ahead of their MFMAs (its scale
+        // register is fetched further down, once the tile before has released it)
+        read_operands(t + 1, (t + 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
-        v16i c = P[idx & 1];
-        if (st == 0) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) c[r] = 0;
+        P[idx & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t & 1][st], b[j][st], st == 0 ? seed : P[idx & 1], 0, 0, 0);
+        asm volatile("" : "+v"(P[idx & 1]));       // the MFMA is issued here, ahead of the rescaling below
+        if (idx > 0) {
+          rescale_quarter(P[(idx - 1) & 1], swf[(idx - 1) % PN], swc[(idx - 1) % PN], S[((idx - 1) / PN) & 1],
+                          acc[(idx - 1) % PN][(idx - 1) / PN], st);
+        } else {
+          rescale_quarter(P[(kTiles - 1) & 1], pend_sw, pend_swc, pend_S, acc[PN - 1][PM - 1], st);
         }
-        P[idx & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[j][st], b[t & 1][st], c, 0, 0, 0);
-        asm volatile("" : "+v"(P[idx & 1]));       // the MFMA is issued here, ahead of the epilogue below
-        if (idx > 0) epilogue_quarter(idx - 1, st);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (j == PN - 1 && t + 1 < PM) {
-        // sam[(t+1)&1] was the scale of token tile t-1, whose last epilogue has just been issued
-        const int row = mw0 + 32 * (t + 1) + m32;
-        sam[(t + 1) & 1] = *reinterpret_cast<const float*>(xl + kActBytes + row * 4);
-      }
+      // S[(t+1)&1] belonged to token tile t-1, whose last rescaling has just been issued
+      if (j == 0 && t + 1 < PM) read_scales(t + 1, (t + 1) & 1);
     }
-#pragma unroll
-    for (int part = 0; part < 4; ++part) epilogue_quarter(PN * PM - 1, part);
+    pend_sw = swf[PN - 1];
+    pend_swc = swc[PN - 1];
+    pend_S = S[(PM - 1) & 1];
 
     store_x((SLOT + 2) % NW);
     __syncthreads();
   };
 
-  // Straight-line body of three groups (no branch around a group: the compiler's
-  // wait-count bookkeeping stays exact only without control flow).  Groups past the
-  // end of the slice run on zeros: their loads are out of range.
+  // Three groups per trip (the ring slots are named statically), each a straight line;
+  // the loop is left between groups (every block inside keeps a single predecessor, so
+  // the compiler's wait-count bookkeeping stays exact).  Requests past the end of the
+  // slice are out of range: zeros, no traffic.
   for (int q = 0; q < ng; q += NW) {
     group_body(std::integral_constant<int, 0>{}, q);
+    if (q + 1 >= ng) break;
     group_body(std::integral_constant<int, 1>{}, q + 1);
+    if (q + 2 >= ng) break;
     group_body(std::integral_constant<int, 2>{}, q + 2);
   }
+#pragma unroll
+  for (int part = 0; part < 4; ++part) rescale_quarter(P[(kTiles - 1) & 1], pend_sw, pend_swc, pend_S, acc[PN - 1][PM - 1], part);
 
-  tile_store32<PN, PM>(p, tc, acc, n0, m0 + mw0);
+  tile_store32<PN, PM, false>(p, tc, acc, n0, m0 + mw0);
 }
 
 }  // namespace qspec

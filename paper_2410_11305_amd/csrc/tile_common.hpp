@@ -74,22 +74,22 @@ __device__ inline uint32_t word_of(const uint4& q, int i) {
 __device__ __forceinline__ float* slice_frag(const TileArgs& p, int c, unsigned blk, int floats_per_block) {
   return p.ws + ((size_t)c * (p.nb * p.mb) + blk) * (size_t)floats_per_block;
 }
-// Output of a wave's PN x PM tiles of 32 x 32 (first output feature n0, first token
-// row mrow0).  MFMA D layout: lane l holds column m = l % 32 and rows 8a + 4h + r
-// (h = l / 32; a, r = 0..3) in register 4a + r, i.e. four runs of four consecutive
-// output features of one token.  S == 1: fp16 stores.  S > 1: see the head of this file.
-template <int PN, int PM>
-__device__ __forceinline__ void tile_store32(const TileArgs& p, const TileCoord& tc, float (&acc)[PN][PM][16],
-                                             int n0, int mrow0) {
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int m32 = lane & 31, h = lane >> 5;
-  if (p.S == 1) {
+// fp16 store of a wave's PN x PM accumulator tiles of 32 x 32 (first output feature n0,
+// first token row mrow0).  Two MFMA D layouts (h = lane / 32; a, r = 0..3; register 4a + r):
+//   LANE_IS_TOKEN   lane holds token m = lane % 32 and features 8a + 4h + r: four runs of
+//                   four consecutive output features of one token (8-byte stores);
+//   !LANE_IS_TOKEN  lane holds feature n = lane % 32 and tokens 8a + 4h + r: per register
+//                   the 32 lanes of a half write 64 contiguous bytes of one token row.
+template <int PN, int PM, bool LANE_IS_TOKEN>
+__device__ __forceinline__ void tile_write_fp16(const TileArgs& p, const float (&acc)[PN][PM][16], int n0, int mrow0) {
+  const int lane = threadIdx.x & 63;
+  const int l32 = lane & 31, h = lane >> 5;
 #pragma unroll
-    for (int j = 0; j < PN; ++j)
+  for (int j = 0; j < PN; ++j)
 #pragma unroll
-      for (int t = 0; t < PM; ++t) {
-        const int m = mrow0 + 32 * t + m32;
+    for (int t = 0; t < PM; ++t) {
+      if (LANE_IS_TOKEN) {
+        const int m = mrow0 + 32 * t + l32;
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
           const int n = n0 + 32 * j + 8 * a + 4 * h;
@@ -100,7 +100,27 @@ __device__ __forceinline__ void tile_store32(const TileArgs& p, const TileCoord&
             *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + n) = out;
           }
         }
+      } else {
+        const int n = n0 + 32 * j + l32;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int m = mrow0 + 32 * t + 8 * a + 4 * h + r;
+            if (m < p.M && n < p.N) p.y[(size_t)m * p.N + n] = float_to_half_bits(acc[j][t][4 * a + r]);
+          }
       }
+    }
+}
+
+// Output of a wave's PN x PM tiles of 32 x 32.  S == 1: fp16 stores.  S > 1: see the
+// head of this file.
+template <int PN, int PM, bool LANE_IS_TOKEN = true>
+__device__ __forceinline__ void tile_store32(const TileArgs& p, const TileCoord& tc, float (&acc)[PN][PM][16],
+                                             int n0, int mrow0) {
+  const int tid = threadIdx.x;
+  if (p.S == 1) {
+    tile_write_fp16<PN, PM, LANE_IS_TOKEN>(p, acc, n0, mrow0);
     return;
   }
   const unsigned blk = (unsigned)(tc.nblk * p.mb + tc.mblk);
@@ -142,22 +162,7 @@ __device__ __forceinline__ void tile_store32(const TileArgs& p, const TileCoord&
           for (int e = 0; e < 8; ++e) { acc[j][tp + t][2 * e] += v[t][e].x; acc[j][tp + t][2 * e + 1] += v[t][e].y; }
       }
   }
-#pragma unroll
-  for (int j = 0; j < PN; ++j)
-#pragma unroll
-    for (int t = 0; t < PM; ++t) {
-      const int m = mrow0 + 32 * t + m32;
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const int n = n0 + 32 * j + 8 * a + 4 * h;
-        if (m < p.M && n < p.N) {
-          uint2 out;
-          out.x = (uint32_t)float_to_half_bits(acc[j][t][4 * a + 0]) | ((uint32_t)float_to_half_bits(acc[j][t][4 * a + 1]) << 16);
-          out.y = (uint32_t)float_to_half_bits(acc[j][t][4 * a + 2]) | ((uint32_t)float_to_half_bits(acc[j][t][4 * a + 3]) << 16);
-          *reinterpret_cast<uint2*>(p.y + (size_t)m * p.N + n) = out;
-        }
-      }
-    }
+  tile_write_fp16<PN, PM, LANE_IS_TOKEN>(p, acc, n0, mrow0);
 }
 
 }  // namespace qspec
