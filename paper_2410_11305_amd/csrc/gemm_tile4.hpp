@@ -28,9 +28,9 @@
 // A workgroup of WGN x WGM wavefronts owns BN x BM outputs (BN = 32*PN*WGN,
 // BM = 32*PM*WGM) over a range of K groups.
 //   - Activations: the BM x 64 B code block of a group and its BM scales go global
-//     -> registers two groups ahead, are widened to int8 once per workgroup and
-//     written to one of three LDS stages at the end of a group; one barrier per
-//     group.  Row layout: 8 slots of 16 bytes (slot kb: low nibbles of k-block kb,
+//     -> registers three groups ahead, are widened to int8 once per workgroup and
+//     written to one of three LDS stages two groups ahead, at the TOP of a group (the
+//     writes land under that group's arithmetic); one barrier per group.  Row layout: 8 slots of 16 bytes (slot kb: low nibbles of k-block kb,
 //     slot 4+kb: high nibbles), slot index xor-ed with act_swizzle(row) so that the
 //     operand reads and the staging writes are free of bank conflicts.
 //   - Weights and their scales: straight into registers in MFMA operand layout
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
   constexpr int kTiles = PN * PM;
   static_assert(kChunks % kThreads == 0 || kChunks < kThreads, "whole passes, or one partial pass");
   static_assert(BM <= kThreads, "one thread per token row stages the activation scale");
-  static_assert(kTiles % 2 == 0, "the last tile of a group and the first of the next use different int32 tiles");
+  static_assert(PM % 2 == 0 && kTiles % 2 == 0, "the last tile of a group and the first of the next use different int32 tiles");
   __shared__ __attribute__((aligned(16))) uint8_t lds[NW * kStageBytes];
 
   const int tid = threadIdx.x;
@@ -214,23 +214,49 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
     }
   };
 
-  // prologue: groups 0 and 1 into stages 0 and 1, the ring filled
+  // this lane's entry of a token tile's scale register: lane i of a row of 16 holds the
+  // scale of the token that accumulator register i belongs to (8 (i/4) + 4 h + i % 4)
+  const int s_row = 8 * ((lane & 15) >> 2) + 4 * h + (lane & 3);
+
+  // A operands: one register quad per MFMA step; the quad of step st is refilled with the
+  // NEXT token tile's step st right after the MFMA that consumed it has been issued (a whole
+  // tile ahead of its use, at half the registers of two complete operand sets)
+  v4i a[4];
+  float S[2];                                    // the sixteen token scales of tile t live in S[t & 1] (see s_row)
+  auto read_operand = [&](const uint8_t* xl, int t, int st) {
+    const int row = mw0 + 32 * t + l32;
+    const int slot = (st == 0 ? h : st == 1 ? h + 4 : st == 2 ? h + 2 : h + 6) ^ act_swizzle(row);
+    a[st] = *reinterpret_cast<const v4i*>(xl + row * 128 + (slot << 4));
+  };
+  auto read_scales = [&](const uint8_t* xl, int t, int buf) {
+    S[buf] = *reinterpret_cast<const float*>(xl + kActBytes + (mw0 + 32 * t + s_row) * 4);
+  };
+
+  // prologue: groups 0 and 1 into stages 0 and 1, group 2 requested (it stays in registers
+  // until the top of group 0), the weight ring filled, the first operands read
   load_x(0);
   store_x(0);
   load_x(1);
 #pragma unroll
   for (int d = 0; d < NW; ++d) load_w(d, d);
   store_x(1);
+  load_x(2);
   __syncthreads();
+#pragma unroll
+  for (int st = 0; st < 4; ++st) read_operand(lds, 0, st);
+  read_scales(lds, 0, 0);
 
-  // this lane's entry of a token tile's scale register: lane i of a row of 16 holds the
-  // scale of the token that accumulator register i belongs to (8 (i/4) + 4 h + i % 4)
-  const int s_row = 8 * ((lane & 15) >> 2) + 4 * h + (lane & 3);
-
+  // Timetable of the activations of group q + 2: requested from memory at the top of group
+  // q - 1, widened into stage (q + 2) % 3 at the top of group q (a whole group after the
+  // request, and with the rest of group q to land before anyone waits for them), published
+  // by the barrier that ends group q, first read at the end of group q + 1 (the operands
+  // of a group's first token tile are fetched under the last tile of the group before).
   auto group_body = [&](auto slot_c, int q) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_c)::value;
     const uint8_t* xl = lds + SLOT * kStageBytes;
-    load_x(q + 2);                               // lands in stage (SLOT + 2) % 3 at the end of this group
+    const uint8_t* xl_next = lds + ((SLOT + 1) % NW) * kStageBytes;
+    store_x((SLOT + 2) % NW);                    // group q + 2; that stage was last read in group q - 1
+    load_x(q + 3);
     __builtin_amdgcn_sched_barrier(0);
 
     // operands of this group: four B operands per 32-row pair, the lane's weight scale
@@ -245,36 +271,19 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
     }
     load_w(SLOT, q + NW);                        // the slot's contents are in b[] and swf[] now
     __builtin_amdgcn_sched_barrier(0);
-
-    v4i a[2][4];                                 // A operands of token tile t live in a[t & 1]
-    float S[2];                                  // its sixteen token scales (see s_row)
-    auto read_operands = [&](int t, int buf) {
-      const int row = mw0 + 32 * t + l32;
-      const int sw = act_swizzle(row);
-      a[buf][0] = *reinterpret_cast<const v4i*>(xl + row * 128 + ((h ^ sw) << 4));
-      a[buf][1] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 4) ^ sw) << 4));
-      a[buf][2] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 2) ^ sw) << 4));
-      a[buf][3] = *reinterpret_cast<const v4i*>(xl + row * 128 + (((h + 6) ^ sw) << 4));
-    };
-    auto read_scales = [&](int t, int buf) {
-      S[buf] = *reinterpret_cast<const float*>(xl + kActBytes + (mw0 + 32 * t + s_row) * 4);
-    };
-    read_operands(0, 0);
-    read_scales(0, 0);
-    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int idx = 0; idx < kTiles; ++idx) {
       const int t = idx / PN, j = idx % PN;
-      if (j == 0 && t + 1 < PM) {
-        // operands of the next token tile, a whole tile ahead of their MFMAs (its scale
-        // register is fetched further down, once the tile before has released it)
-        read_operands(t + 1, (t + 1) & 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
-        P[idx & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[t & 1][st], b[j][st], st == 0 ? seed : P[idx & 1], 0, 0, 0);
+        P[idx & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b[j][st], st == 0 ? seed : P[idx & 1], 0, 0, 0);
         asm volatile("" : "+v"(P[idx & 1]));       // the MFMA is issued here, ahead of the rescaling below
+        if (j == PN - 1) {
+          // this step's operand of the next token tile: of this group, or the first tile of
+          // the next group (whose stage the barrier before this group has published)
+          if (t + 1 < PM) read_operand(xl, t + 1, st);
+          else read_operand(xl_next, 0, st);
+        }
         if (idx > 0) {
           rescale_quarter(P[(idx - 1) & 1], swf[(idx - 1) % PN], swc[(idx - 1) % PN], S[((idx - 1) / PN) & 1],
                           acc[(idx - 1) % PN][(idx - 1) / PN], st);
@@ -284,13 +293,12 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
         __builtin_amdgcn_sched_barrier(0);
       }
       // S[(t+1)&1] belonged to token tile t-1, whose last rescaling has just been issued
-      if (j == 0 && t + 1 < PM) read_scales(t + 1, (t + 1) & 1);
+      if (j == 0 && t + 1 < PM) read_scales(xl, t + 1, (t + 1) & 1);
     }
     pend_sw = swf[PN - 1];
     pend_swc = swc[PN - 1];
     pend_S = S[(PM - 1) & 1];
-
-    store_x((SLOT + 2) % NW);
+    read_scales(xl_next, 0, 0);                  // S[0] was token tile PM-2's: released
     __syncthreads();
   };
 
