@@ -28,8 +28,8 @@ HIPCC_FLAGS = [
 # issued after them; a register spill would put stores into that sequence (stores
 # complete out of order with loads), so such an instance must not be shipped.  The
 # streaming kernels are held to the same rule (a spill in their loop costs more than
-# the instance gains); the draft-mode tiled kernel is checked by its own list below.
-NO_SPILL_KERNELS = ("gemm_tile16w_kernel", "gemm_stream_kernel")
+# the instance gains), and so is the draft-mode tiled kernel.
+NO_SPILL_KERNELS = ("gemm_tile16w_kernel", "gemm_stream_kernel", "gemm_tile4w_kernel")
 
 
 def spilling_kernels(report: str, names) -> list:

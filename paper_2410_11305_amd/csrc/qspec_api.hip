@@ -330,13 +330,11 @@ constexpr TileShape kShapes16[] = {     // verify mode (gemm_tile16w_kernel): TN
     {1, 2, 8, 1, 4, 4, 1},   // 6: 256 x 64, eight wavefronts, four activation stages
 };
 constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile4w_kernel): TN, TMW count 32 x 32 tiles; NW = NS = 3
-    {1, 4, 4, 1, 3, 3, 2},   // 0: 128 x 128
+    {1, 4, 4, 1, 3, 3, 2},   // 0: 128 outputs x 128 tokens
     {1, 2, 4, 1, 3, 3, 2},   // 1: 128 x 64
-    {1, 4, 2, 1, 3, 3, 2},   // 2: 64 x 128
-    {1, 2, 2, 1, 3, 3, 2},   // 3: 64 x 64
-    {1, 4, 4, 1, 3, 3, 1},   // 4: 128 x 128, one workgroup per compute unit
+    {1, 2, 2, 1, 3, 3, 2},   // 2: 64 x 64
 };
-constexpr int kNumTileShapes = 5;
+constexpr int kNumTileShapes = 3;
 constexpr int kNumShapes16 = 7;
 struct TilePlan {
   int shape;      // index into the mode's shape table
@@ -366,7 +364,12 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
     // mode takes 128 x 128 blocks when they fill the chip at least twice over and
     // 128 x 64 blocks (three workgroups per compute unit) otherwise.
     if (w4a4) {
-      shape = 1;
+      // 128 x 128 blocks (a weight operand feeds four token tiles instead of two) once they
+      // fill the chip almost twice over; below that the smaller block's better balance wins
+      // (22016 x 4096 at 512 tokens: 80.0 -> 71.3 us; 57344 x 8192 at 128 / 512: 114 -> 106,
+      // 374 -> 325 us; 12288 x 4096 at 512, 384 blocks: 45.5 vs 46.1 us)
+      const int blocks128 = ((N + 127) / 128) * ((M + 127) / 128);
+      shape = (M > 64 && blocks128 >= 440) ? 0 : 1;
     } else {
       const int blocks128 = ((N + 127) / 128) * ((M + 127) / 128);
       const int blocks64 = ((N + 127) / 128) * ((M + 63) / 64);
@@ -446,9 +449,7 @@ int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s
     switch (plan.shape) {
       case 0: return launch_tile4w_inst<1, 4, 4, 1, 2>(a, s);
       case 1: return launch_tile4w_inst<1, 2, 4, 1, 2>(a, s);
-      case 2: return launch_tile4w_inst<1, 4, 2, 1, 2>(a, s);
-      case 3: return launch_tile4w_inst<1, 2, 2, 1, 2>(a, s);
-      default: return launch_tile4w_inst<1, 4, 4, 1, 1>(a, s);
+      default: return launch_tile4w_inst<1, 2, 2, 1, 2>(a, s);
     }
   }
   switch (plan.shape) {
