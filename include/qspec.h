@@ -220,6 +220,35 @@ int qspec_gemm_w4a16_noalloc(const void* packed, const void* x_f16,
                              void* y_f16, void* stream);
 
 /*
+ * The MLP of a decoder block in the draft pass as ONE persistent launch (paper Sec. 3.1,
+ * draft phase: every linear layer of the draft pass runs in W4A4 on activations quantised
+ * on the fly; Sec. 3.2: the method's gain rests on a fast draft pass):
+ *   gate_up = W4A4( qa_h, sa_h ; packed_gate_up )            fp16 [M, 2I], gate first
+ *   (qa_i, sa_i) = what qspec_silu_mul_quant writes for gate_up (rotate = 0)
+ *   y = W4A4( qa_i, sa_i ; packed_down )                     fp16 [M, H]
+ * i.e. exactly qspec_gemm_w4a4, qspec_silu_mul_quant, qspec_gemm_w4a4 in a row, for
+ * 1 <= M <= 32 tokens.
+ *   packed_gate_up  blob of the [2I, H] gate/up weight;  packed_down  blob of the [H, I] weight;
+ *   qa_h, sa_h      quantised block input for K = H (qspec_rmsnorm_quant / qspec_quant_act);
+ *   gate_up_f16, qa_i, sa_i, y_f16   outputs (the first three are also how the stages talk);
+ *   workspace       qspec_mlp_draft_workspace_bytes(...) bytes of counters, ZERO before the
+ *                   first use; every successful call leaves them zero;
+ *   status_word     device int32 the caller set to 0.  The launch is one workgroup per
+ *                   compute unit and needs all of them resident together (an otherwise idle
+ *                   GPU).  A workgroup that has waited for the others longer than a bounded
+ *                   number of polls (about 0.1 s) writes 1 there and exits; y_f16 is then
+ *                   invalid and the workspace must be zeroed again.  Every kernel exits.
+ * Returns QSPEC_ERR_UNSUPPORTED for shapes outside the kernel (M > 32; more than 6 gate/up
+ * or 2 down tiles of 16 outputs per compute unit; more than 96 KB of down-projection
+ * weights per compute unit, e.g. I > 12288 with H <= 4096): use the separate calls.
+ */
+size_t qspec_mlp_draft_workspace_bytes(int M, int H, int I, int group);
+int qspec_mlp_draft(const void* packed_gate_up, const void* packed_down,
+                    const uint8_t* qa_h, const float* sa_h, int M, int H, int I, int group,
+                    void* gate_up_f16, uint8_t* qa_i, float* sa_i, void* y_f16,
+                    void* workspace, size_t workspace_bytes, int* status_word, void* stream);
+
+/*
  * Debug entry: the exact per-group integer partial sums of the draft product
  * for output columns n0 .. n0+n_count-1 (n0 and n_count multiples of 16):
  *   partials[m, n - n0, j] = P[m,n,j], int32 [M, n_count, G] row-major.
@@ -278,6 +307,7 @@ int qspec_kv_overwrite(const void* kv_verify_f16, const int32_t* n_accept, const
  *                             workgroup, K-slices, token-row blocks of the streaming kernels
  *   "QSPEC_STREAM_MAX_W4A4"   largest M the draft-mode streaming kernel takes (32..128)
  *   "QSPEC_TILE_W4A4",    "QSPEC_TILE_W4A16"     value "shape,S": workgroup shape, K-slices
+ *   "QSPEC_MLP_SPIN"          polls before a workgroup of qspec_mlp_draft gives up waiting
  * `value` NULL (or unparsable) clears that override; both are host strings.  The same
  * names are read from the environment once, at the library's first use; no entry point
  * reads the environment afterwards.  A forced plan that names no existing kernel instance

@@ -22,7 +22,7 @@ EXPORTS = (
     "qspec_accept_workspace_bytes", "qspec_greedy_accept", "qspec_kv_overwrite",
     "qspec_rmsnorm_quant", "qspec_silu_mul_quant", "qspec_hadamard_quant",
     "qspec_reorder_quant", "qspec_debug_set_plan",
-    "qspec_gemm_w4a16_noalloc",
+    "qspec_gemm_w4a16_noalloc", "qspec_mlp_draft", "qspec_mlp_draft_workspace_bytes",
 )
 
 
@@ -84,6 +84,10 @@ def lib() -> ctypes.CDLL:
     L.qspec_reorder_quant.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, vp]
     L.qspec_gemm_w4a16_noalloc.restype = ci
     L.qspec_gemm_w4a16_noalloc.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+    L.qspec_mlp_draft_workspace_bytes.restype = sz
+    L.qspec_mlp_draft_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    L.qspec_mlp_draft.restype = ci
+    L.qspec_mlp_draft.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp, vp]
     L.qspec_debug_set_plan.restype = ci
     L.qspec_debug_set_plan.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
     _lib = L
@@ -294,6 +298,36 @@ def gemm_w4a16_noalloc(packed: torch.Tensor, x: torch.Tensor, N: int, y: torch.T
                                           M, N, K, group, _dev(y, torch.float16, "y"), _stream()),
            "qspec_gemm_w4a16_noalloc")
     return y
+
+
+def mlp_draft_workspace_bytes(M: int, H: int, I: int, group: int = GROUP) -> int:
+    return lib().qspec_mlp_draft_workspace_bytes(M, H, I, group)
+
+
+def mlp_draft(packed_gate_up: torch.Tensor, packed_down: torch.Tensor, qa_h: torch.Tensor, sa_h: torch.Tensor,
+              H: int, I: int, workspace: torch.Tensor, status: torch.Tensor, gate_up: torch.Tensor = None,
+              qa_i: torch.Tensor = None, sa_i: torch.Tensor = None, y: torch.Tensor = None, group: int = GROUP):
+    """The draft-pass MLP of a block in one persistent launch.  workspace: zero-filled uint8 of
+    mlp_draft_workspace_bytes; status: int32 [1] the caller zeroed (1 afterwards: the launch gave up).
+    Returns (gate_up fp16 [M, 2I], qa_i, sa_i, y fp16 [M, H])."""
+    M = qa_h.shape[0]
+    dev = qa_h.device
+    if gate_up is None:
+        gate_up = torch.empty((M, 2 * I), dtype=torch.float16, device=dev)
+    if qa_i is None:
+        qa_i = torch.empty((M, I // 2), dtype=torch.uint8, device=dev)
+    if sa_i is None:
+        sa_i = torch.empty((M, I // group), dtype=torch.float32, device=dev)
+    if y is None:
+        y = torch.empty((M, H), dtype=torch.float16, device=dev)
+    _check(lib().qspec_mlp_draft(_dev(packed_gate_up, torch.uint8, "packed_gate_up"), _dev(packed_down, torch.uint8, "packed_down"),
+                                 _dev(qa_h, torch.uint8, "qa_h"), _dev(sa_h, torch.float32, "sa_h"), M, H, I, group,
+                                 _dev(gate_up, torch.float16, "gate_up"), _dev(qa_i, torch.uint8, "qa_i"),
+                                 _dev(sa_i, torch.float32, "sa_i"), _dev(y, torch.float16, "y"),
+                                 _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                 _dev(status, torch.int32, "status"), _stream()),
+           "qspec_mlp_draft")
+    return gate_up, qa_i, sa_i, y
 
 
 def gemm_w4a4_partials(packed: torch.Tensor, qa: torch.Tensor, N: int, n0: int, n_count: int,

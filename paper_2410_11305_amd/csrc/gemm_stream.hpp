@@ -59,9 +59,11 @@ struct GroupRegs {
 };
 
 // Issue every load of group g (valid == false: all offsets out of range, no traffic).
+// wlds != nullptr: the weight tiles of this workgroup were copied to LDS beforehand, tile j
+// of group g at wlds + (j * G + g) * 1024, and are read from there.
 template <bool W4A4, int TM, int NT>
 __device__ inline void load_group(GroupRegs<W4A4, TM, NT>& R, const StreamRsrc& rs, const StreamArgs& p, int g,
-                                  bool valid, int T0, int nt_valid, int lane) {
+                                  bool valid, int T0, int nt_valid, int lane, const uint8_t* wlds = nullptr) {
   const int r16 = lane & 15, kb = lane >> 4;
   // activations first: loads return in order, and the (L2-resident) activations
   // must not queue behind the HBM weight tiles
@@ -89,7 +91,11 @@ __device__ inline void load_group(GroupRegs<W4A4, TM, NT>& R, const StreamRsrc& 
   for (int j = 0; j < NT; ++j) {
     const bool ok = valid && j < nt_valid;
     const uint32_t T = (uint32_t)(T0 + j);
-    R.w[j] = buf_load16_stream(rs.codes, ok ? (T * p.G + g) * 1024u + lane * 16u : kOutOfRange);
+    if (wlds != nullptr) {
+      R.w[j] = ok ? *reinterpret_cast<const uint4*>(wlds + ((size_t)(j * p.G + g) * 1024u + lane * 16u)) : uint4{0u, 0u, 0u, 0u};
+    } else {
+      R.w[j] = buf_load16_stream(rs.codes, ok ? (T * p.G + g) * 1024u + lane * 16u : kOutOfRange);
+    }
     if (!pair_scales(NT)) R.sw[j] = buf_load8(rs.scales, ok ? ((uint32_t)g * p.N + T * 16u + 4u * kb) * 2u : kOutOfRange);
   }
 }

@@ -14,6 +14,7 @@
 #include "gemm_stream.hpp"
 #include "gemm_tile16.hpp"
 #include "gemm_tile4.hpp"
+#include "mlp_chain.hpp"
 #include "pack.hpp"
 #include "producers.hpp"
 #include "quant_act.hpp"
@@ -100,11 +101,13 @@ struct PlanOverrides {
   int stream_max[2] = {0, 0};         // 0: the default bound
   bool tile_set[2] = {false, false};
   int tile[2][2] = {{0, 0}, {0, 0}};
+  unsigned mlp_spin = 0;              // 0: the default number of polls of the persistent MLP kernel's wait
 };
 
 // value == nullptr (or unparsable) clears the override named `name`; false: unknown name.
 bool apply_override(PlanOverrides& o, const char* name, const char* value) {
   if (strcmp(name, "QSPEC_KERNEL") == 0) { o.generic = value && strcmp(value, "generic") == 0; return true; }
+  if (strcmp(name, "QSPEC_MLP_SPIN") == 0) { o.mlp_spin = value ? (unsigned)strtoul(value, nullptr, 10) : 0u; return true; }
   for (int w4a4 = 0; w4a4 < 2; ++w4a4) {
     if (strcmp(name, w4a4 ? "QSPEC_STREAM_W4A4" : "QSPEC_STREAM_W4A16") == 0) {
       int* f = o.stream[w4a4];
@@ -131,7 +134,7 @@ bool apply_override(PlanOverrides& o, const char* name, const char* value) {
 
 constexpr const char* kOverrideNames[] = {"QSPEC_KERNEL", "QSPEC_STREAM_W4A4", "QSPEC_STREAM_W4A16",
                                           "QSPEC_STREAM_MAX_W4A4", "QSPEC_STREAM_MAX_W4A16",
-                                          "QSPEC_TILE_W4A4", "QSPEC_TILE_W4A16"};
+                                          "QSPEC_TILE_W4A4", "QSPEC_TILE_W4A16", "QSPEC_MLP_SPIN"};
 
 PlanOverrides& overrides() {
   static PlanOverrides o = [] {
@@ -505,6 +508,53 @@ __global__ __launch_bounds__(256) void clear_tickets_kernel(unsigned* tickets, i
   if (i < n) tickets[i] = 0u;
 }
 
+// ---------------------------------------------------------------- persistent draft-pass MLP
+// Workgroups of the persistent launch: one per compute unit of the current device (looked up
+// once per device).  0: the query failed.
+int mlp_workgroups() {
+  static int cus[kMaxDevices];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
+    cus[dev] = n;
+  }
+  return cus[dev];
+}
+
+constexpr size_t kMlpCounterBytes = 16384;
+constexpr unsigned kMlpDefaultSpin = 200000;      // polls of about a microsecond each before a workgroup gives up
+
+// Tiles per workgroup of the two projections for nwg workgroups; false: the shape does not fit the kernel.
+bool mlp_plan(int M, int H, int I, int nwg, int* nt1, int* nt2) {
+  if (M < 1 || M > 32 || nwg < 1) return false;
+  const int tiles1 = 2 * I / 16, tiles2 = H / 16, G2 = I / kGroup;
+  const int need1 = (tiles1 + nwg - 1) / nwg, need2 = (tiles2 + nwg - 1) / nwg;
+  *nt1 = need1 <= 2 ? 2 : need1 <= 4 ? 4 : 6;
+  *nt2 = need2 <= 1 ? 1 : 2;
+  if (need1 > 6 || need2 > 2) return false;
+  if (need2 * G2 > kMlpWBufTiles) return false;               // the down-projection tiles of a workgroup must fit LDS
+  if ((size_t)(G2 + 2) * sizeof(unsigned) > kMlpCounterBytes) return false;
+  return true;
+}
+
+template <int TM, int NT1>
+int launch_mlp_nt2(const MlpArgs& a, int nt2, int nwg, hipStream_t s) {
+  if (nt2 == 1) hipLaunchKernelGGL((mlp_draft_kernel<TM, NT1, 1>), dim3(nwg), dim3(kStreamWaves * 64), 0, s, a);
+  else hipLaunchKernelGGL((mlp_draft_kernel<TM, NT1, 2>), dim3(nwg), dim3(kStreamWaves * 64), 0, s, a);
+  return QSPEC_OK;
+}
+template <int TM>
+int launch_mlp(const MlpArgs& a, int nt1, int nt2, int nwg, hipStream_t s) {
+  switch (nt1) {
+    case 2: return launch_mlp_nt2<TM, 2>(a, nt2, nwg, s);
+    case 4: return launch_mlp_nt2<TM, 4>(a, nt2, nwg, s);
+    case 6: return launch_mlp_nt2<TM, 6>(a, nt2, nwg, s);
+    default: return QSPEC_ERR_UNSUPPORTED;
+  }
+}
+
 inline bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
 
 inline int check_accept_shape(int B, int gamma, int V) {
@@ -758,6 +808,45 @@ int qspec_gemm_w4a16_noalloc(const void* packed, const void* x_f16, int M, int N
                        static_cast<unsigned*>(ws), kMaxTickets);
   }
   return qspec_gemm_w4a16(packed, x_f16, M, N, K, group, y_f16, ws, kScratchBytes, stream);
+}
+
+size_t qspec_mlp_draft_workspace_bytes(int M, int H, int I, int group) {
+  if (check_shape(M, H, I, group) != QSPEC_OK || check_shape(M, 2 * I, H, group) != QSPEC_OK) return 0;
+  return kMlpCounterBytes;
+}
+
+int qspec_mlp_draft(const void* packed_gate_up, const void* packed_down, const uint8_t* qa_h, const float* sa_h,
+                    int M, int H, int I, int group, void* gate_up_f16, uint8_t* qa_i, float* sa_i, void* y_f16,
+                    void* workspace, size_t workspace_bytes, int* status_word, void* stream) {
+  if (!packed_gate_up || !packed_down || !qa_h || !sa_h || !gate_up_f16 || !qa_i || !sa_i || !y_f16 || !workspace || !status_word)
+    return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, 2 * I, H, group)) return st;
+  if (int st = check_shape(M, H, I, group)) return st;
+  if (misaligned(packed_gate_up) || misaligned(packed_down) || misaligned(qa_h) || misaligned(sa_h) || misaligned(gate_up_f16) ||
+      misaligned(qa_i) || misaligned(sa_i) || misaligned(y_f16) || misaligned(workspace) || misaligned4(status_word))
+    return QSPEC_ERR_ALIGN;
+  if (workspace_bytes < kMlpCounterBytes) return QSPEC_ERR_WORKSPACE;
+  if (int st = check_device()) return st;
+  const int nwg = mlp_workgroups();
+  if (nwg <= 0) return QSPEC_ERR_HIP;
+  int nt1 = 0, nt2 = 0;
+  if (!mlp_plan(M, H, I, nwg, &nt1, &nt2)) return QSPEC_ERR_UNSUPPORTED;
+  MlpArgs a{};
+  a.codes1 = static_cast<const uint4*>(packed_gate_up);
+  a.scales1T = blob_scales(packed_gate_up, 2 * I, H);
+  a.qa_h = qa_h; a.sa_h = sa_h;
+  a.y_gu = static_cast<uint16_t*>(gate_up_f16);
+  a.qa_i = qa_i; a.sa_i = sa_i;
+  a.codes2 = static_cast<const uint4*>(packed_down);
+  a.scales2T = blob_scales(packed_down, H, I);
+  a.y = static_cast<uint16_t*>(y_f16);
+  a.counters = static_cast<unsigned*>(workspace);
+  a.status = status_word;
+  a.M = M; a.N1 = 2 * I; a.K1 = H; a.N2 = H; a.K2 = I;
+  a.spin_limit = overrides().mlp_spin ? overrides().mlp_spin : kMlpDefaultSpin;   // QSPEC_MLP_SPIN: tests of the give-up path
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (int st = (M <= 16 ? launch_mlp<1>(a, nt1, nt2, nwg, s) : launch_mlp<2>(a, nt1, nt2, nwg, s))) return st;
+  return launch_status();
 }
 
 int qspec_gemm_w4a4_partials(const void* packed, const uint8_t* qa, int M, int N, int K, int group,
