@@ -550,6 +550,27 @@ class Bench:
             out["draft_mlp_block_us"] = {
                 "fused_producers": round(self.time_runner(self.make_runner(mlp_fused), reps, 2) / L * 1e6, 2),
                 "torch_producers_plus_quant_act": round(self.time_runner(self.make_runner(mlp_unfused), reps, 2) / L * 1e6, 2)}
+            # the same block with gate/up -> SiLU*up + quantiser -> down as ONE persistent launch
+            # (2 launches per block instead of 4), where the kernel takes the shape
+            if Md <= 32:
+                try:
+                    ws_m = B.alloc_workspace(B.mlp_draft_workspace_bytes(Md, Kh, Ii))
+                    st_m = torch.zeros(1, dtype=torch.int32, device=dev)
+
+                    def mlp_persistent():
+                        for l in range(L):
+                            B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1])
+                            B.mlp_draft(blobs[i_gu][l], blobs[3][l], pq_h[0], pq_h[1], Kh, Ii, ws_m, st_m, ygu, pq_i[0], pq_i[1], ydn)
+
+                    t_p = self.time_runner(self.make_runner(mlp_persistent), reps, 2) / L * 1e6
+                    out["draft_mlp_block_us"]["persistent_launch"] = round(t_p, 2)
+                    out["draft_mlp_block_us"]["persistent_launch_gave_up"] = int(st_m.item())
+                    mlp_bytes = alg_bytes_w4a4(Md, 2 * Ii, Kh) + alg_bytes_w4a4(Md, Kh, Ii)
+                    out["draft_mlp_block_us"]["hbm_frac_of_the_two_gemms"] = {
+                        "separate_launches": round(mlp_bytes / (out["draft_mlp_block_us"]["fused_producers"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                        "persistent_launch": round(mlp_bytes / (t_p * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+                except B.QSpecError as e:
+                    out["draft_mlp_block_us"]["persistent_launch"] = str(e)
         out["silu_mul_quant_GBps"] = round((Md * Ii * 4 + Md * Ii // 2 + Md * (Ii // 128) * 4) / out["silu_mul_quant_us"] / 1e3, 1)
         return out
 

@@ -170,15 +170,17 @@ __global__ __launch_bounds__(kStreamWaves * 64, 1) void mlp_draft_kernel(MlpArgs
 #pragma unroll
         for (int r = 0; r < 4; ++r) facc[j][t][r] = 0.0f;
     mlp_stream<TM, NT1>(a, rs, t_lo, nt1, wave, lane, facc, nullptr);
-    mlp_reduce_store<TM, NT1, true>(facc, red, p.y_gu, p.N1, M, t_lo, nt1, wave, lane);
+    mlp_reduce_store<TM, NT1, false>(facc, red, p.y_gu, p.N1, M, t_lo, nt1, wave, lane);
   }
-  // publish the tiles: every wave's write-through stores acknowledged, then the counters
-  __builtin_amdgcn_s_waitcnt(0x0f70);                    // vmcnt(0)
+  // publish the tiles: plain stores (adjacent tiles merge into whole lines in L2; 8-byte
+  // write-through stores were measured at 3 to 10 us for this step), the barrier, then
+  // counter increments with RELEASE semantics (one L2 write-back per workgroup)
   __syncthreads();
   if (tid == 0) {
     // tile t (gate: t < I/16, up: the same index + I/16) belongs to quantisation group (t % (I/16)) / 8
     const int tilesI = I / 16;
     int n = 0, t = t_lo;
+    if (t < t_hi) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     while (t < t_hi) {
       const int j = (t % tilesI) / 8;
       int c = 0;
@@ -195,34 +197,35 @@ __global__ __launch_bounds__(kStreamWaves * 64, 1) void mlp_draft_kernel(MlpArgs
   __syncthreads();
 
   // ------------------------------------------------------------ SiLU(gate) * up + quantiser for the groups this workgroup completed
-  for (int i = 0; i < n_todo; ++i) {
-    const int j = todo[i];
-    const int m = tid >> 4, l = tid & 15;                 // 16 lanes per (token, group); M <= 32 tokens
-    const bool live = m < M;
-    uint64_t g2[2] = {0, 0}, u2[2] = {0, 0};
-    if (live) {
-      const uint64_t* gp = reinterpret_cast<const uint64_t*>(p.y_gu + (size_t)m * p.N1 + (size_t)j * kGroup + 8 * l);
-      const uint64_t* up = reinterpret_cast<const uint64_t*>(p.y_gu + (size_t)m * p.N1 + (size_t)I + (size_t)j * kGroup + 8 * l);
-      g2[0] = __hip_atomic_load(gp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      g2[1] = __hip_atomic_load(gp + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      u2[0] = __hip_atomic_load(up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      u2[1] = __hip_atomic_load(up + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    const uint4 graw = {(uint32_t)g2[0], (uint32_t)(g2[0] >> 32), (uint32_t)g2[1], (uint32_t)(g2[1] >> 32)};
-    const uint4 uraw = {(uint32_t)u2[0], (uint32_t)(u2[0] >> 32), (uint32_t)u2[1], (uint32_t)(u2[1] >> 32)};
-    const v8h gh = __builtin_bit_cast(v8h, graw);
-    const v8h uh = __builtin_bit_cast(v8h, uraw);
-    float v[8];
+  // 16 lanes per (token, group): 32 such units per pass over the workgroup's 512 threads
+  {
+    const int n_units = M * n_todo;
+    for (int u0 = 0; u0 < n_units; u0 += 32) {
+      const int unit = u0 + (tid >> 4), l = tid & 15;
+      const bool live = unit < n_units;
+      const int gi = live ? unit / M : 0, m = live ? unit - gi * M : 0;
+      const int j = todo[gi];
+      uint4 graw = {0u, 0u, 0u, 0u}, uraw = {0u, 0u, 0u, 0u};
+      if (live) {
+        graw = *reinterpret_cast<const uint4*>(p.y_gu + (size_t)m * p.N1 + (size_t)j * kGroup + 8 * l);
+        uraw = *reinterpret_cast<const uint4*>(p.y_gu + (size_t)m * p.N1 + (size_t)I + (size_t)j * kGroup + 8 * l);
+      }
+      const v8h gh = __builtin_bit_cast(v8h, graw);
+      const v8h uh = __builtin_bit_cast(v8h, uraw);
+      float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const double g = (double)(float)gh[e];
-      const float s = (float)(g / (1.0 + exp(-g)));
-      v[e] = (float)(_Float16)rounded_f32(s * (float)uh[e]);
+      for (int e = 0; e < 8; ++e) {
+        const double g = (double)(float)gh[e];
+        const float s = (float)(g / (1.0 + exp(-g)));
+        v[e] = (float)(_Float16)rounded_f32(s * (float)uh[e]);
+      }
+      const size_t idx = (size_t)m * (size_t)(I / 8) + (size_t)j * 16 + l;   // word index in [M][I/8]
+      finish_unit(v, false, live, idx, reinterpret_cast<uint32_t*>(p.qa_i), p.sa_i, nullptr);
     }
-    const size_t idx = (size_t)m * (size_t)(I / 8) + (size_t)j * 16 + l;   // word index in [M][I/8]
-    finish_unit(v, false, live, idx, reinterpret_cast<uint32_t*>(p.qa_i), p.sa_i, nullptr);
-    __syncthreads();                                       // the whole group is written ...
-    if (tid == 0) __hip_atomic_fetch_add(done, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);   // ... and published
+    if (n_todo > 0) {
+      __syncthreads();                                     // the groups are written ...
+      if (tid == 0) __hip_atomic_fetch_add(done, (unsigned)n_todo, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);   // ... and published
+    }
   }
 
   // ------------------------------------------------------------ prefetch: this workgroup's down-projection weights -> LDS
@@ -246,7 +249,7 @@ __global__ __launch_bounds__(kStreamWaves * 64, 1) void mlp_draft_kernel(MlpArgs
     while (true) {
       if (__hip_atomic_load(done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= (unsigned)G2) { ok = true; break; }
       if (++n >= p.spin_limit) break;
-      __builtin_amdgcn_s_sleep(8);
+      __builtin_amdgcn_s_sleep(2);
     }
     if (ok) {
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
