@@ -32,6 +32,14 @@ __device__ inline uint2 buf_load8(rsrc_t r, uint32_t off) {
 __device__ inline uint16_t buf_load_u16(rsrc_t r, uint32_t off) {
   return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
 }
+// three consecutive floats (4-byte aligned; each component is range-checked on its own)
+struct float3_t { float x, y, z; };
+__device__ inline float3_t buf_load_f32x3(rsrc_t r, uint32_t off) {
+  typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
+  const u32x3 v = __builtin_amdgcn_raw_buffer_load_b96(r, off, 0, 0);
+  const uint32_t a = v.x, b = v.y, c = v.z;      // (copies: bit_cast of a vector element lvalue reads element 0)
+  return float3_t{__builtin_bit_cast(float, a), __builtin_bit_cast(float, b), __builtin_bit_cast(float, c)};
+}
 __device__ inline float buf_load_f32(rsrc_t r, uint32_t off) {
   return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
 }

@@ -130,8 +130,15 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
 
   // ---- activations: global -> registers (rows past M lie past the end of the buffer)
   uint4 xs[U];
-  float sas = 0.0f;
+  // The activation scales of a token row are consecutive in memory along the groups, and a
+  // load of one scale per row touches one cache line per lane: three groups are fetched at
+  // a time (groups 3k .. 3k+2 at the top of group 3k-3), a third of the line visits.
+  float sas[NW] = {0.0f, 0.0f, 0.0f};
   const uint32_t idle_sa = (uint32_t)((BM - 1 - tid) >> 31) << 31;                 // tid >= BM
+  auto load_sa3 = [&](int q) {                                                     // groups q, q+1, q+2 of this slice
+    const float3_t v = buf_load_f32x3(r_sa, (((uint32_t)(m0 + tid) * G + (uint32_t)(g0 + q)) * 4u) | past_end(q) | idle_sa);
+    sas[0] = v.x; sas[1] = v.y; sas[2] = v.z;
+  };
   auto load_x = [&](int q) {
     const uint32_t gone = past_end(q);
     const int g = g0 + q;
@@ -142,9 +149,8 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
       const uint32_t idle = (uint32_t)((kChunks - 1 - idx) >> 31) << 31;           // idx >= kChunks
       xs[u] = buf_load16(r_act, ((uint32_t)(m0 + row) * (uint32_t)(p.K / 2) + (uint32_t)g * 64u + c * 16u) | gone | idle);
     }
-    sas = buf_load_f32(r_sa, (((uint32_t)(m0 + tid) * G + g) * 4u) | gone | idle_sa);
   };
-  auto store_x = [&](int stage) {
+  auto store_x = [&](int stage) {                                                  // stage = (group index in the slice) % 3
     uint8_t* base = lds + stage * kStageBytes;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -161,7 +167,7 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
         *reinterpret_cast<v4i*>(base + row * 128 + ((s1 ^ sw) << 4)) = hi_first ? q.lo : q.hi;
       }
     }
-    if (tid < BM) *reinterpret_cast<float*>(base + kActBytes + tid * 4) = sas * 0.00390625f;   // 2^-8, exact
+    if (tid < BM) *reinterpret_cast<float*>(base + kActBytes + tid * 4) = sas[stage] * 0.00390625f;   // 2^-8, exact
   };
 
   // ---- weights: ring of NW groups; per 32-row pair two 16-byte pieces and the scale
@@ -234,6 +240,7 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
 
   // prologue: groups 0 and 1 into stages 0 and 1, group 2 requested (it stays in registers
   // until the top of group 0), the weight ring filled, the first operands read
+  load_sa3(0);
   load_x(0);
   store_x(0);
   load_x(1);
@@ -256,6 +263,7 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
     const uint8_t* xl = lds + SLOT * kStageBytes;
     const uint8_t* xl_next = lds + ((SLOT + 1) % NW) * kStageBytes;
     store_x((SLOT + 2) % NW);                    // group q + 2; that stage was last read in group q - 1
+    if (SLOT == 0) load_sa3(q + 3);              // (its last scale, of group q + 2, has just been used)
     load_x(q + 3);
     __builtin_amdgcn_sched_barrier(0);
 
