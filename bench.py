@@ -367,6 +367,8 @@ class Bench:
         L.ceil_mfma.argtypes = [ci, vp, ci, ci, vp, vp]
         L.ceil_empty.restype = ci
         L.ceil_empty.argtypes = [vp]
+        L.ceil_quant_prologue.restype = ci
+        L.ceil_quant_prologue.argtypes = [vp, ci, ci, ci, vp, vp]
         return L
 
     def bare_reads(self, lins, blobs, L, Md):
@@ -423,6 +425,26 @@ class Bench:
             t = self.time_runner(self.make_runner(f), 5, 2)
             tops = blocks * waves * iters * 16 * flop / t / 1e12
             out[key] = dict(TOPS=round(tops, 1), frac_of_published_peak=round(tops / peak, 4), us=round(t * 1e6, 1))
+        # what a quantiser fused into the small-M draft GEMM would add to that kernel (every one of
+        # its workgroups would quantise all of x), against the separate quantiser launch it would save
+        B = self.B
+        fused = {}
+        n_rep = 16
+        for M, K in ((8, 4096), (8, 11008), (32, 4096), (32, 11008)):
+            x = torch.randn((M, K), device=dev, generator=gen).half()
+            scratch = torch.empty(256 * (M * K // 2 + M * K // 32), dtype=torch.uint8, device=dev)
+            qa = torch.empty((M, K // 2), dtype=torch.uint8, device=dev)
+            sa = torch.empty((M, K // 128), dtype=torch.float32, device=dev)
+
+            def f(x=x, M=M, K=K, scratch=scratch):
+                for _ in range(n_rep):
+                    rc = C.ceil_quant_prologue(x.data_ptr(), M, K, 256, scratch.data_ptr(), s())
+                    assert rc == 0, rc
+            t_in = self.time_runner(self.make_runner(f), 5, 2) / n_rep
+            t_sep = self.time_runner(self.make_runner(lambda x=x, qa=qa, sa=sa: [B.quant_act(x, qa, sa) for _ in range(n_rep)]), 5, 2) / n_rep
+            fused[f"M{M}.K{K}"] = dict(every_workgroup_quantises_all_of_x_us=round(t_in * 1e6, 2),
+                                       separate_quant_act_launch_us=round(t_sep * 1e6, 2))
+        out["quantiser_inside_small_M_draft_gemm"] = fused
         return out
 
     # ---- optional yardstick: the vendor library's plain fp16 GEMM on the verify-mode shapes
@@ -600,34 +622,28 @@ class Bench:
                 scales = synth.weight_scales(ci, i, lin.N, lin.K)[:n_rows]
             host.append((rng_codes, scales, synth.activations(ci, i, Md, lin.K, verify=False),
                          synth.activations(ci, i, Mv, lin.K, verify=True)))
-        done = [0] * len(lins)
+        done = [0] * len(lins)          # columns done per layer (counted on through repeats of the sampled rows)
         c0 = time.perf_counter()
         quantised = {}
         bytes_done = 0.0
-        while True:
-            progressed = False
+        while time.perf_counter() - c0 < budget_s:
             for i, lin in enumerate(lins):
                 codes, scales, hxd, hxv = host[i]
-                if done[i] + chunk > codes.shape[0]:
-                    continue
                 if i not in quantised:
                     quantised[i] = orc.quant_act(hxd)
                     bytes_done += alg_bytes_quant(Md, lin.K)
                 q, s = quantised[i]
-                cols = np.arange(done[i], done[i] + chunk)
+                start = done[i] % (codes.shape[0] - codes.shape[0] % chunk or codes.shape[0])
+                cols = np.arange(start, min(start + chunk, codes.shape[0]))
                 orc.gemm_w4a4_columns(q, s, codes, scales, cols)
                 orc.gemm_w4a16_columns(hxv, codes, scales, cols)
-                done[i] += chunk
-                progressed = True
-                frac = chunk / lin.N
-                bytes_done += frac * (alg_bytes_w4a4(Md, lin.N, lin.K) + alg_bytes_w4a16(Mv, lin.N, lin.K))
+                done[i] += len(cols)
+                bytes_done += len(cols) / lin.N * (alg_bytes_w4a4(Md, lin.N, lin.K) + alg_bytes_w4a16(Mv, lin.N, lin.K))
                 if time.perf_counter() - c0 >= budget_s:
                     break
-            if time.perf_counter() - c0 >= budget_s or not progressed:
-                break
         c_t = time.perf_counter() - c0
         return dict(value=round(bytes_done / c_t / 1e12, 6), unit="TB/s", cores=int(cores), kind="oracle",
-                    sample=f"the first {', '.join(str(d) for d in done)} output columns of the "
+                    sample=f"{', '.join(str(d) for d in done)} output columns (chunks of {chunk}) of the "
                            f"{len(lins)} layer(s) of one decoder block (quantiser + draft product at M={Md}, verify "
                            f"product at M={Mv}), {c_t:.1f} s of the NumPy float64 oracle on BLAS threads",
                     seconds=round(c_t, 2))

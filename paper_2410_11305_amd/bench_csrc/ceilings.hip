@@ -16,9 +16,17 @@
 //                      least that y += float(P) * sa * sw takes), which is what bounds
 //                      the draft mode at large M whatever the kernel does around it.
 //   ceil_empty         an empty kernel (launch + drain cost inside a captured graph).
+//   ceil_quant_prologue  what fusing the activation quantiser into the small-M draft GEMM
+//                      would add to that kernel: every workgroup of such a GEMM covers all of K
+//                      and would have to quantise ALL of x itself.  Here `blocks` workgroups
+//                      of 8 wavefronts each quantise the whole fp16 [M, K] tensor with the
+//                      library's own quantiser arithmetic (into scratch of their own), to be
+//                      set against the separate quantiser launch it would replace.
 // All pointers are device pointers; work is enqueued on `stream`; 0 = ok.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "quant_act.hpp"
 
 namespace {
 
@@ -153,6 +161,22 @@ __global__ __launch_bounds__(512, 1) void mfma_loop_kernel(const uint4* operands
 
 __global__ void empty_kernel() {}
 
+__global__ __launch_bounds__(512) void quant_prologue_kernel(const uint4* x, size_t n_words, uint32_t* qa_scratch, float* sa_scratch) {
+  uint32_t* qa = qa_scratch + (size_t)blockIdx.x * n_words;
+  float* sa = sa_scratch + (size_t)blockIdx.x * (n_words / 16);
+  for (size_t base = 0; base < n_words; base += 512) {        // n_words is a multiple of 16: a group is live or not as a whole
+    const size_t idx = base + threadIdx.x;
+    const bool live = idx < n_words;
+    uint4 raw = {0u, 0u, 0u, 0u};
+    if (live) raw = x[idx];
+    float v[8];
+    const qspec::v8h h = __builtin_bit_cast(qspec::v8h, raw);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (float)h[e];
+    qspec::quantise_unit(v, live, idx, qa, sa);
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -177,6 +201,17 @@ int ceil_mfma(int kind, const void* operands, int blocks, int iters, void* out, 
   else if (kind == 1) hipLaunchKernelGGL(mfma_loop_kernel<1>, dim3(blocks), dim3(512), 0, s, op, iters, o);
   else if (kind == 2) hipLaunchKernelGGL(mfma_loop_kernel<2>, dim3(blocks), dim3(512), 0, s, op, iters, o);
   else return 1;
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+// x: fp16 [M, K] (K a multiple of 128); scratch: blocks * (M*K/2 + M*K/32) bytes.
+int ceil_quant_prologue(const void* x, int M, int K, int blocks, void* scratch, void* stream) {
+  if (!x || !scratch || M < 1 || K < 128 || K % 128 || blocks < 1) return 1;
+  const size_t n_words = (size_t)M * K / 8;
+  uint32_t* qa = static_cast<uint32_t*>(scratch);
+  float* sa = reinterpret_cast<float*>(qa + (size_t)blocks * n_words);
+  hipLaunchKernelGGL(quant_prologue_kernel, dim3(blocks), dim3(512), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(x), n_words, qa, sa);
   return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 

@@ -69,7 +69,7 @@ def build(verbose: bool = True) -> str:
     spilled = spilling_kernels(res.stdout, NO_SPILL_KERNELS)
     if spilled:
         raise RuntimeError("kernels that must not spill registers do: " + ", ".join(spilled))
-    cmd = [hipcc(), *HIPCC_FLAGS, "-o", CEIL_LIB_PATH, *CEIL_SOURCES]
+    cmd = [hipcc(), *HIPCC_FLAGS, "-I", os.path.join(HERE, "csrc"), "-o", CEIL_LIB_PATH, *CEIL_SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
