@@ -275,7 +275,15 @@ inline size_t stream_ws_bytes(const StreamPlan& p) {
 bool tile_override(bool w4a4, int* shape, int* S);
 
 bool use_stream(bool w4a4, int M, int N, int K) {
-  if (M <= stream_base_max(w4a4)) return true;
+  if (M <= stream_base_max(w4a4)) {
+    // Draft mode, 48 to 64 tokens, very wide layers (170 and more blocks of 128 outputs): the
+    // tiled kernel is faster than the streaming one (22016 x 4096 at 64 tokens 26.8 -> 23.4 us,
+    // 27648 x 5120: 36.4 -> 29.2, 57344 x 8192: 101.5 -> 68.4; at 48 tokens equal or better;
+    // narrower layers stay with the streaming kernel: 12288 x 4096 at 64 tokens 13.7 vs 17.3 us)
+    const PlanOverrides& ov = overrides();
+    const bool wide_draft = w4a4 && M >= 48 && N >= 170 * 128 && ov.stream_fields[1] == 0 && ov.stream_max[1] == 0;
+    return !wide_draft;
+  }
   int shape, S;
   if (tile_override(w4a4, &shape, &S)) return false;      // a forced tile shape means the tiled kernel
   return plan_stream(w4a4, M, N, K).nt > 0;
@@ -402,11 +410,14 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
     // doubling still pays while the workgroups stay resident together (two per unit).
     const TileShape& t0 = shape_of(w4a4, shape);
     const int blocks = ((N + 32 * t0.TN * t0.WGN - 1) / (32 * t0.TN * t0.WGN)) * ((M + 32 * t0.TMW * t0.WGM - 1) / (32 * t0.TMW * t0.WGM));
+    const int resident = t0.OCC >= 2 ? 2 * kNumCU : kNumCU;     // workgroups that run at once
+    // (the draft-mode kernel fills both places of a compute unit with slices: 160 blocks of
+    // 10240 x 8192 at 128 tokens 35.7 us unsliced, 28.4 us in three slices)
     S = kNumCU / blocks;
+    if (w4a4 && S < 4 && resident / blocks > S) S = resident / blocks < 4 ? resident / blocks : 4;   // (eight slices of 64 blocks: 24.6 us, four: 21.7 us)
     if (S > 8) S = 8;
     while (S > 1 && G / S < 8) --S;
     if (S < 1) S = 1;
-    const int resident = t0.OCC >= 2 ? 2 * kNumCU : kNumCU;     // workgroups that run at once
     // (only while the doubled count still fits: 448 blocks of 57344 x 8192 at 128 draft tokens
     // in two slices, 896 workgroups for 512 places, took 121 us against 103 us unsliced)
     while (S < 8 && blocks * S * 2 <= resident && G / (2 * S) >= 32) S *= 2;
