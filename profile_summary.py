@@ -11,6 +11,11 @@ copy that bench.py issues before its timed region (__amd_rocclr_copyBuffer).
 
 usage: python profile_summary.py <in_dir> <out_dir> [tag]
 (the digits in the tag name the bench.py --config the runs were made with)
+
+If <in_dir> also holds sqa_counter_collection.csv / sqb_counter_collection.csv (two more
+--pmc runs, see CMD_SQ), a table of those counters per GEMM kernel is written as
+<tag>_sq_counters.txt: instruction counts per wave, matrix-unit and vector-ALU share of
+the SIMD cycles, LDS bank conflicts.
 """
 from __future__ import annotations
 
@@ -25,6 +30,12 @@ CMD_KT = ("rocprofv3 --kernel-trace --stats -f csv -d <dir> -o kt -- "
           "python3 bench.py --config {cfg} --steps 5 --warmup 1 --no-cpu-baseline --no-extra")
 CMD_PMC = ("rocprofv3 --pmc {c} -f csv -d <dir> -o {o} -- "
            "python3 bench.py --config {cfg} --steps 2 --warmup 1 --no-cpu-baseline --no-extra --no-graph")
+
+
+SQ_A = "SQ_WAVES SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_LDS SQ_LDS_BANK_CONFLICT"
+SQ_B = "SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS SQ_WAIT_INST_ANY SQ_WAIT_ANY SQ_ACTIVE_INST_ANY SQ_INSTS_SALU SQ_INSTS_VMEM GRBM_GUI_ACTIVE"
+CMD_SQ = ("rocprofv3 --pmc {c} -f csv -d <dir> -o {o} -- "
+          "python3 bench.py --config {cfg} --steps 2 --warmup 1 --no-cpu-baseline --no-extra --no-graph")
 
 
 def _short(name: str) -> str:
@@ -113,7 +124,47 @@ def main(in_dir: str, out_dir: str, tag: str = "bench_config2") -> None:
         f.write("\n")
 
 
+def sq_table(in_dir: str, out_dir: str, tag: str) -> None:
+    """Mean per dispatch of the SQ counters of the two optional runs, per GEMM kernel, with
+    the ratios that read directly: vector / matrix instructions per wave, share of SIMD
+    cycles the matrix unit is busy (MFMA busy cycles / (4 SIMDs x 256 CUs x GUI-active cycles
+    per XCD)), wave time spent issuing / waiting."""
+    paths = [os.path.join(in_dir, f"{o}_counter_collection.csv") for o in ("sqa", "sqb")]
+    if not all(os.path.exists(q) for q in paths):
+        return
+    cfg = "".join(ch for ch in tag if ch.isdigit()) or "2"
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for q in paths:
+        with open(q) as f:
+            for r in csv.DictReader(f):
+                agg[_short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    lines = [f"# SQ counters per dispatch (mean), {tag}",
+             f"# commands: {CMD_SQ.format(c=SQ_A, o='sqa', cfg=cfg)}",
+             f"#           {CMD_SQ.format(c=SQ_B, o='sqb', cfg=cfg)}"]
+    for k in sorted(agg):
+        if not k.startswith("gemm_"):
+            continue
+        m = {c: sum(v) / len(v) for c, v in agg[k].items()}
+        lines.append(f"  {k}  ({len(next(iter(agg[k].values())))} dispatches)")
+        for c in sorted(m):
+            lines.append(f"      {c:28s} {m[c]:16.1f}")
+        w = m.get("SQ_WAVES", 0.0)
+        if w > 0 and "GRBM_GUI_ACTIVE" in m:
+            simd_cycles = m["GRBM_GUI_ACTIVE"] / 8.0 * 4 * 256        # the counter adds the 8 XCDs
+            lines.append(f"      -> per wave: {m.get('SQ_INSTS_VALU', 0) / w:.0f} vector, {m.get('SQ_INSTS_MFMA', 0) / w:.0f} matrix, "
+                         f"{m.get('SQ_INSTS_LDS', 0) / w:.0f} LDS, {m.get('SQ_INSTS_VMEM', 0) / w:.0f} vector-memory instructions")
+            lines.append(f"      -> matrix unit busy {100 * m.get('SQ_VALU_MFMA_BUSY_CYCLES', 0) / simd_cycles:.1f} % of SIMD cycles, "
+                         f"vector ALU issuing {100 * 4 * m.get('SQ_ACTIVE_INST_VALU', 0) / simd_cycles:.1f} %; "
+                         f"LDS bank-conflict cycles {m.get('SQ_LDS_BANK_CONFLICT', 0):.0f}")
+            if m.get("SQ_WAVE_CYCLES"):
+                lines.append(f"      -> of a wave's lifetime: issuing {100 * m.get('SQ_ACTIVE_INST_ANY', 0) / m['SQ_WAVE_CYCLES']:.0f} %, "
+                             f"waiting on a counter {100 * m.get('SQ_WAIT_INST_ANY', 0) / m['SQ_WAVE_CYCLES']:.0f} %")
+    with open(os.path.join(out_dir, f"{tag}_sq_counters.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+
+
 if __name__ == "__main__":
     if len(sys.argv) < 3:
         sys.exit(__doc__)
     main(*sys.argv[1:4])
+    sq_table(sys.argv[1], sys.argv[2], sys.argv[3] if len(sys.argv) > 3 else "bench_config2")
