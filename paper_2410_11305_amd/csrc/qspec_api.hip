@@ -387,18 +387,27 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       // 128 x 64 blocks: with at most one workgroup per compute unit the instance with
       // four activation stages hides more latency (measured 23.5 -> 21.4 us at 128 tokens
       // on 12288 x 4096); with more workgroups than compute units the three-per-unit instance
-      // (128 x 128 blocks also when one per compute unit exists and K is long enough for the
-      // two K-slices that make it two: 28672 -> 8192 at 512 tokens 254 -> 236 us)
-      const bool big = M > 64 && (blocks128 >= 2 * kNumCU || (blocks128 >= kNumCU && G >= 128));
+      // (128 x 128 blocks also from 120 blocks on when K is long enough for the two K-slices that
+      // then fill the chip: 28672 -> 8192 at 512 tokens 254 -> 236 us, at 256 tokens 141 -> 134 us;
+      // 11008 -> 4096 at 512: 60.3 -> 58.8 us; 13824 -> 5120 at 384: 71.0 -> 68.9 us)
+      const bool big = M > 64 && (blocks128 >= 2 * kNumCU || (blocks128 >= 120 && G >= 86));
       shape = big ? 0 : (blocks64 <= kNumCU ? 3 : 2);
       // 256 x 128 blocks on eight wavefronts (one workgroup per compute unit) halve the
       // activation bytes a compute unit pulls per output (the global -> LDS transfers of x are
-      // 19 % of the 128 x 128 instance's time), but with one workgroup per unit a ragged
-      // last round costs a whole round: only when the rounds come out (almost) full
-      // (16384 x 8192 at 512 tokens: 134.6 -> 125.0 us; 57344 x 8192: no gain at 87.5 %)
+      // 19 % of the 128 x 128 instance's time), but with one workgroup per unit a ragged round
+      // costs a whole round.  Taken when ONE round is at least 58 % full, counting the two
+      // K-slices a long K allows (10240 x 8192 at 512 tokens, 160 blocks: 103.4 -> 94.5 us;
+      // 15360 x 5120 at 384, 180 blocks: 70.8 -> 66.5; 12288 x 4096 at 512, 192 blocks: 59.6 ->
+      // 57.5; 28672 -> 8192 at 512, 128 blocks in two slices: 241 -> 229; 128 blocks unsliced
+      // lose: 8192 x 8192 at 512 tokens 75 -> 89 us), or when several rounds are at least 85 %
+      // full (57344 x 8192 at 256 tokens, 448 blocks: 255 -> 236 us; at 512 tokens, 896 blocks
+      // = 3.5 rounds: equal; 324 and 344 blocks lose 10 %).
       const int blocks256 = ((N + 255) / 256) * ((M + 127) / 128);
       const int rounds256 = (blocks256 + kNumCU - 1) / kNumCU;
-      if (big && M >= 256 && blocks256 * 100 >= rounds256 * kNumCU * 95) shape = 4;
+      if (M >= 256) {
+        const int s256 = (blocks256 * 2 <= kNumCU && G >= 64) ? 2 : 1;      // the slices the rule below will cut
+        if (rounds256 == 1 ? blocks256 * s256 >= 150 : blocks256 * 100 >= rounds256 * kNumCU * 85) shape = 4;
+      }
     }
     // K-slices (measured: the exchange costs 4-8 us).  They pay while ALL workgroups
     // still run at once on compute units of their own: S = the largest count (not only
