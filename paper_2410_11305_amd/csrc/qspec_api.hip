@@ -374,13 +374,50 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
     // by its per-group scaling arithmetic and does best on 128 x 64 blocks; the verify
     // mode takes 128 x 128 blocks when they fill the chip at least twice over and
     // 128 x 64 blocks (three workgroups per compute unit) otherwise.
+    bool s_chosen = false;
     if (w4a4) {
-      // 128 x 128 blocks (a weight operand feeds four token tiles instead of two) once they
-      // fill the chip almost twice over; below that the smaller block's better balance wins
-      // (22016 x 4096 at 512 tokens: 80.0 -> 71.3 us; 57344 x 8192 at 128 / 512: 114 -> 106,
-      // 374 -> 325 us; 12288 x 4096 at 512, 384 blocks: 45.5 vs 46.1 us)
-      const int blocks128 = ((N + 127) / 128) * ((M + 127) / 128);
-      shape = (M > 64 && blocks128 >= 440) ? 0 : 1;
+      // Two block sizes, 128 x 128 (a weight operand feeds four token tiles) and 128 x 64, and up
+      // to four K-slices: the plan that comes closest to filling the 512 places of the chip
+      // (two workgroups per compute unit) in ONE round wins.  From sweeps over the Llama-shaped
+      // layers at 64 to 512 tokens: 13824 -> 5120 at 512 tokens 79.5 us (128 x 64, unsliced, 320
+      // workgroups) -> 63.0 (128 x 128 in three slices, 480); 28672 -> 8192 at 384: 160 -> 140;
+      // 10240 x 8192 at 256: 49.5 -> 44.9; at 128: 35.7 -> 28.4.  Ties go to the larger block when
+      // its slices keep at least 48 groups, else to the plan with fewer slices (the exchange costs
+      // 4-8 us).  Problems too large for one round run unsliced, on 128 x 128 blocks from 420
+      // blocks on (27648 x 5120 at 256 tokens, 432 blocks: 70.0 -> 60.7 us).
+      const int nb128 = (N + 127) / 128;
+      const int blocks[2] = {nb128 * ((M + 127) / 128), nb128 * ((M + 63) / 64)};
+      const int places = 2 * kNumCU;
+      int sl[2] = {1, 1};
+      double fill[2] = {-1.0, -1.0};
+      for (int i = 0; i < 2; ++i) {
+        if (blocks[i] > places || (i == 0 && M <= 64)) continue;       // (a 128-token block is half empty at 64 tokens)
+        int c = places / blocks[i];
+        if (c > 4) c = 4;
+        while (c > 1 && G / c < 8) --c;
+        sl[i] = c;
+        fill[i] = (double)blocks[i] * c / places;
+      }
+      if (fill[0] < 0 && fill[1] < 0) {
+        shape = (M > 64 && blocks[0] >= 420) ? 0 : 1;
+        S = 1;
+      } else if (fill[1] < 0) {
+        shape = blocks[0] >= 420 ? 0 : 1;
+        S = shape == 0 ? 1 : 1;
+      } else if (fill[0] < 0) {
+        shape = 1;
+        S = sl[1];
+      } else {
+        const double d = fill[0] - fill[1];
+        if (d > 0.05) shape = 0;
+        else if (d < -0.05) shape = 1;
+        else shape = (G / sl[0] >= 48 || sl[0] <= sl[1]) ? 0 : 1;
+        S = sl[shape];
+        // a very long K carries twice the slices even past one round (28672 -> 8192 at 384
+        // tokens: two slices 148.7 us, four 139.8)
+        if (fill[shape] <= 0.75 && S == 2 && G / 4 >= 48) S = 4;
+      }
+      s_chosen = true;
     } else {
       const int blocks128 = ((N + 127) / 128) * ((M + 127) / 128);
       const int blocks64 = ((N + 127) / 128) * ((M + 63) / 64);
@@ -417,19 +454,17 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
     // 25.2 us unsliced, 29.6 us in two slices; 128 blocks of 8192 x 8192 at 128 tokens:
     // 40.9 -> 29.7 us).  With very long K (at least 32 groups per slice after doubling)
     // doubling still pays while the workgroups stay resident together (two per unit).
-    const TileShape& t0 = shape_of(w4a4, shape);
-    const int blocks = ((N + 32 * t0.TN * t0.WGN - 1) / (32 * t0.TN * t0.WGN)) * ((M + 32 * t0.TMW * t0.WGM - 1) / (32 * t0.TMW * t0.WGM));
-    const int resident = t0.OCC >= 2 ? 2 * kNumCU : kNumCU;     // workgroups that run at once
-    // (the draft-mode kernel fills both places of a compute unit with slices: 160 blocks of
-    // 10240 x 8192 at 128 tokens 35.7 us unsliced, 28.4 us in three slices)
-    S = kNumCU / blocks;
-    if (w4a4 && S < 4 && resident / blocks > S) S = resident / blocks < 4 ? resident / blocks : 4;   // (eight slices of 64 blocks: 24.6 us, four: 21.7 us)
-    if (S > 8) S = 8;
-    while (S > 1 && G / S < 8) --S;
-    if (S < 1) S = 1;
-    // (only while the doubled count still fits: 448 blocks of 57344 x 8192 at 128 draft tokens
-    // in two slices, 896 workgroups for 512 places, took 121 us against 103 us unsliced)
-    while (S < 8 && blocks * S * 2 <= resident && G / (2 * S) >= 32) S *= 2;
+    if (!s_chosen) {
+      const TileShape& t0 = shape_of(w4a4, shape);
+      const int blocks = ((N + 32 * t0.TN * t0.WGN - 1) / (32 * t0.TN * t0.WGN)) * ((M + 32 * t0.TMW * t0.WGM - 1) / (32 * t0.TMW * t0.WGM));
+      const int resident = t0.OCC >= 2 ? 2 * kNumCU : kNumCU;     // workgroups that run at once
+      S = kNumCU / blocks;
+      if (S > 8) S = 8;
+      while (S > 1 && G / S < 8) --S;
+      if (S < 1) S = 1;
+      // (only while the doubled count still fits)
+      while (S < 8 && blocks * S * 2 <= resident && G / (2 * S) >= 32) S *= 2;
+    }
   }
   const TileShape& t = shape_of(w4a4, shape);
   const int edge = 32;                  // MFMA tile edge
