@@ -442,7 +442,7 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       const int blocks256 = ((N + 255) / 256) * ((M + 127) / 128);
       const int rounds256 = (blocks256 + kNumCU - 1) / kNumCU;
       if (M >= 128) {                                  // (57344 x 8192 at 128 tokens, 224 blocks: 135 -> 123 us)
-        const int s256 = (blocks256 * 2 <= kNumCU && G >= 64) ? 2 : 1;      // the slices the rule below will cut
+        const int s256 = (M >= 256 && blocks256 * 2 <= kNumCU && G >= 64) ? 2 : 1;      // the slices the rule below will cut
         if (rounds256 == 1 ? blocks256 * s256 >= 150 : blocks256 * 100 >= rounds256 * kNumCU * 85) shape = 4;
       }
     }
