@@ -413,12 +413,32 @@ class Bench:
         ops_f16 = torch.randn((8 << 20,), device=dev, generator=gen).half()                       # 16 MiB of random fp16
         ops_i8 = torch.randint(-128, 128, (16 << 20,), dtype=torch.int8, device=dev, generator=gen)
         ops_const = torch.full((8 << 20,), 1.0, dtype=torch.float16, device=dev)
+        # operands distributed as the kernels' own: a thread of the loop takes units 0..3 of its
+        # 8 x 16 bytes as A and units 4..7 as B.  Verify mode: A = fp16(code * scale), B = the
+        # input recipe's activations (one channel in a hundred 20x); draft mode: 16 * code, the
+        # form the draft kernels feed the matrix unit
+        # (the clock this part holds depends on how many operand bits toggle)
+        n = (1 << 20) // 8
+        w16 = (torch.randint(-8, 8, (n, 4, 8), device=dev, generator=gen).float() *
+               (torch.rand((n, 4, 1), device=dev, generator=gen) * 0.008 + 0.002).half().float()).half()
+        x16 = (torch.randn((n, 4, 8), device=dev, generator=gen) *
+               torch.where(torch.rand((n, 4, 8), device=dev, generator=gen) < 0.01, 20.0, 1.0)).half()
+        ops_verify = torch.cat([w16, x16], dim=1).contiguous()
+        ops_draft = (torch.cat([torch.randint(-7, 8, (n, 4, 16), dtype=torch.int8, device=dev, generator=gen),
+                                torch.randint(-8, 8, (n, 4, 16), dtype=torch.int8, device=dev, generator=gen)], dim=1) * 16).contiguous()
+        ops_zero = torch.zeros((8 << 20,), dtype=torch.float16, device=dev)
         sink = torch.zeros(16, dtype=torch.float32, device=dev)
         blocks, iters, waves = 256, 2000, 8
-        for key, kind, ops, flop, peak in (("mfma_f16_32x32x16_random_operands", 0, ops_f16, 2 * 32 * 32 * 16, 2500.0),
-                                           ("mfma_f16_32x32x16_constant_operands", 0, ops_const, 2 * 32 * 32 * 16, 2500.0),
-                                           ("mfma_i8_32x32x32_random_operands", 1, ops_i8, 2 * 32 * 32 * 32, 5000.0),
-                                           ("mfma_i8_plus_group_rescale_2fma_per_output", 2, ops_i8, 2 * 32 * 32 * 32, 5000.0)):
+        f16_flop, i8_flop = 2 * 32 * 32 * 16, 2 * 32 * 32 * 32
+        C.ceil_mfma(0, ops_f16.data_ptr(), blocks, iters, sink.data_ptr(), s())       # (the first loop after start-up times slow)
+        for key, kind, ops, flop, peak in (("mfma_f16_32x32x16_random_operands", 0, ops_f16, f16_flop, 2500.0),
+                                           ("mfma_f16_32x32x16_constant_operands", 0, ops_const, f16_flop, 2500.0),
+                                           ("mfma_f16_32x32x16_zero_operands", 0, ops_zero, f16_flop, 2500.0),
+                                           ("mfma_f16_32x32x16_verify_mode_operands", 0, ops_verify, f16_flop, 2500.0),
+                                           ("mfma_i8_32x32x32_random_operands", 1, ops_i8, i8_flop, 5000.0),
+                                           ("mfma_i8_32x32x32_draft_mode_operands", 1, ops_draft, i8_flop, 5000.0),
+                                           ("mfma_i8_plus_group_rescale_2fma_per_output", 2, ops_i8, i8_flop, 5000.0),
+                                           ("mfma_i8_draft_mode_operands_plus_group_rescale", 2, ops_draft, i8_flop, 5000.0)):
             def f(kind=kind, ops=ops):
                 rc = C.ceil_mfma(kind, ops.data_ptr(), blocks, iters, sink.data_ptr(), s())
                 assert rc == 0, rc
