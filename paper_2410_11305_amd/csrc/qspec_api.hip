@@ -344,8 +344,9 @@ constexpr TileShape kShapes4[] = {      // draft mode (gemm_tile4w_kernel): TN, 
     {1, 4, 4, 1, 3, 3, 2},   // 0: 128 outputs x 128 tokens
     {1, 2, 4, 1, 3, 3, 2},   // 1: 128 x 64
     {1, 2, 2, 1, 3, 3, 2},   // 2: 64 x 64
+    {1, 4, 8, 1, 3, 3, 1},   // 3: 256 x 128, eight wavefronts, one workgroup per compute unit
 };
-constexpr int kNumTileShapes = 3;
+constexpr int kNumTileShapes = 4;
 constexpr int kNumShapes16 = 7;
 struct TilePlan {
   int shape;      // index into the mode's shape table
@@ -414,6 +415,32 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
         // a very long K carries twice the slices even past one round (28672 -> 8192 at 384
         // tokens: two slices 148.7 us, four 139.8)
         if (fill[shape] <= 0.75 && S == 2 && G / 4 >= 48) S = 4;
+      }
+      // 256 x 128 blocks on eight wavefronts, one workgroup per compute unit: the activation
+      // codes of a group are widened and staged once for twice the outputs, and half the
+      // activation bytes enter the unit.  As in the verify mode a ragged round costs a whole
+      // round, so (both plans timed alternately in one process): one round at least 60 % full
+      // unsliced (57344 x 8192 at 128 tokens, 224 blocks: 115.4 -> 105.0 us; 10240 x 8192 at 512,
+      // 160 blocks: 84.8 -> 72.7; 22016 x 4096 at 256, 172 blocks: 46.6 -> 40.9; 15360 x 5120 at
+      // 384: 57.7 -> 50.0), or at least 90 % full in up to three K-slices of at least 21 groups
+      // or four of at least 48 (28672 -> 8192 at 512 tokens, two slices: 179.6 -> 164.7; at 256,
+      // four: 101.9 -> 93.8; 10240 x 8192 at 256, three: 47.4 -> 44.3; slices of 16 groups lose:
+      // 12288 x 4096 at 256 tokens 31.6 -> 34.5), or several rounds at least 85 % full (57344 x
+      // 8192 at 256 tokens: 188.3 -> 176.8; at 512, 3.5 rounds: equal; 1.3 rounds lose 6-8 %).
+      const int mb128 = (M + 127) / 128;
+      if (M > 96 && M * 4 >= mb128 * 128 * 3) {
+        const int blocks3 = ((N + 255) / 256) * mb128;
+        if (blocks3 <= kNumCU) {
+          int c = kNumCU / blocks3;
+          if (c > 4) c = 4;
+          if (c == 4 && G / 4 < 48) c = 3;             // (four slices of 21 groups: 4096 x 11008 at 512 tokens 45.1 -> 47.1 us)
+          while (c > 1 && G / c < 21) --c;
+          const int full = blocks3 * c * 100;
+          if (c == 1 ? full >= kNumCU * 60 : full >= kNumCU * 90) { shape = 3; S = c; }
+        } else {
+          const int rounds3 = (blocks3 + kNumCU - 1) / kNumCU;
+          if (blocks3 * 100 >= rounds3 * kNumCU * 85) { shape = 3; S = 1; }
+        }
       }
       s_chosen = true;
     } else {
@@ -507,7 +534,8 @@ int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s
     switch (plan.shape) {
       case 0: return launch_tile4w_inst<1, 4, 4, 1, 2>(a, s);
       case 1: return launch_tile4w_inst<1, 2, 4, 1, 2>(a, s);
-      default: return launch_tile4w_inst<1, 2, 2, 1, 2>(a, s);
+      case 2: return launch_tile4w_inst<1, 2, 2, 1, 2>(a, s);
+      default: return launch_tile4w_inst<1, 4, 8, 1, 1>(a, s);
     }
   }
   switch (plan.shape) {

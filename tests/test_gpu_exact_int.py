@@ -83,7 +83,7 @@ def test_stream_instances_integer_stage_bit_exact(env, plan, tm, nt, S):
 
 
 @pytest.mark.parametrize("S", [1, 2])
-@pytest.mark.parametrize("shape", range(3))
+@pytest.mark.parametrize("shape", range(4))
 def test_tile_shapes_integer_stage_bit_exact(env, plan, shape, S):
     torch, B = env
     M, N, G = 150, 304, 9                                # ragged M and N, three rounds of the 3-deep ring

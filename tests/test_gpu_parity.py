@@ -203,7 +203,7 @@ def test_tile_kernels_every_workgroup_shape(env, plan, shape, S):
     count (7) that does not divide by the slice count."""
     torch, B = env
     M, N, K = 150, 304, 896
-    plan("QSPEC_TILE_W4A4", f"{shape % 3},{S}")      # 3 draft-mode shapes, 7 verify-mode shapes
+    plan("QSPEC_TILE_W4A4", f"{shape % 4},{S}")      # 4 draft-mode shapes, 7 verify-mode shapes
     plan("QSPEC_TILE_W4A16", f"{shape},{S}")
     codes, scales, x = synth.generic_case(600 + shape, M, N, K)
     blob = B.pack_weights(dev(torch, codes), dev(torch, scales))
