@@ -452,7 +452,9 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       // (128 x 128 blocks also from 120 blocks on when K is long enough for the two K-slices that
       // then fill the chip: 28672 -> 8192 at 512 tokens 254 -> 236 us, at 256 tokens 141 -> 134 us;
       // 11008 -> 4096 at 512: 60.3 -> 58.8 us; 13824 -> 5120 at 384: 71.0 -> 68.9 us)
-      const bool big = M > 64 && (blocks128 >= 2 * kNumCU || (blocks128 >= 120 && G >= 86));
+      // (and from one 128 x 128 block per compute unit on: 8192 x 8192 at 512 tokens, 256 blocks:
+      // 74.1 us on 512 blocks of 128 x 64, 73.1 on 256 x 128 in two K-slices, 70.7 here)
+      const bool big = M > 64 && (blocks128 >= 2 * kNumCU || (blocks128 >= 120 && G >= 86) || (M >= 128 && blocks128 >= kNumCU));
       shape = big ? 0 : (blocks64 <= kNumCU ? 3 : 2);
       // 256 x 128 blocks on eight wavefronts (one workgroup per compute unit) halve the
       // activation bytes a compute unit pulls per output (the global -> LDS transfers of x are
@@ -467,8 +469,11 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       const int blocks256 = ((N + 255) / 256) * ((M + 127) / 128);
       const int rounds256 = (blocks256 + kNumCU - 1) / kNumCU;
       if (M >= 128) {                                  // (57344 x 8192 at 128 tokens, 224 blocks: 135 -> 123 us)
-        const int s256 = (M >= 256 && blocks256 * 2 <= kNumCU && G >= 64) ? 2 : 1;      // the slices the rule below will cut
-        if (rounds256 == 1 ? blocks256 * s256 >= 150 : blocks256 * 100 >= rounds256 * kNumCU * 85) shape = 4;
+        int s256 = (M >= 256 && blocks256 * 2 <= kNumCU && G >= 64) ? 2 : 1;      // the slices the rule below will cut
+        if (s256 == 2 && blocks128 >= kNumCU && G < 86) s256 = 1;                 // (unsliced 128 x 128 blocks fill the chip: see above)
+        // (from three rounds on they must be 95 % full: 57344 x 8192 at 512 tokens, 3.5 rounds: 441 us, 128 x 128 blocks 435)
+        const int need_pct = rounds256 <= 2 ? 85 : 95;
+        if (rounds256 == 1 ? blocks256 * s256 >= 150 : blocks256 * 100 >= rounds256 * kNumCU * need_pct) shape = 4;
       }
     }
     // K-slices (measured: the exchange costs 4-8 us).  They pay while ALL workgroups
@@ -477,8 +482,10 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
     // groups per slice.  Beyond that the extra workgroups queue behind the first ones
     // and only the exchange is added (172 blocks of a 22016-wide layer at 64 tokens:
     // 25.2 us unsliced, 29.6 us in two slices; 128 blocks of 8192 x 8192 at 128 tokens:
-    // 40.9 -> 29.7 us).  With very long K (at least 32 groups per slice after doubling)
-    // doubling still pays while the workgroups stay resident together (two per unit).
+    // 40.9 -> 29.7 us).  With very long K (at least 43 groups per slice after doubling:
+    // 11008 -> 4096 at 512 tokens 60.3 -> 58.8 us; 32 or 40 groups per slice lose, 8192 x 8192
+    // at 512 tokens 70.7 -> 75.4, 8192 x 10240: 93.0 -> 97.0) doubling still pays while the
+    // workgroups stay resident together (two per unit).
     if (!s_chosen) {
       const TileShape& t0 = shape_of(w4a4, shape);
       const int blocks = ((N + 32 * t0.TN * t0.WGN - 1) / (32 * t0.TN * t0.WGN)) * ((M + 32 * t0.TMW * t0.WGM - 1) / (32 * t0.TMW * t0.WGM));
@@ -488,7 +495,7 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       while (S > 1 && G / S < 8) --S;
       if (S < 1) S = 1;
       // (only while the doubled count still fits)
-      while (S < 8 && blocks * S * 2 <= resident && G / (2 * S) >= 32) S *= 2;
+      while (S < 8 && blocks * S * 2 <= resident && G / (2 * S) >= 43) S *= 2;
     }
   }
   const TileShape& t = shape_of(w4a4, shape);
