@@ -166,24 +166,43 @@ class Bench:
         ws_bytes = max([B.workspace_bytes(M, l.N, l.K) for l in lins for M in (Md, Mv)] + [16])
         ws = B.alloc_workspace(ws_bytes)
         nl = len(lins)
+        # Layers whose draft-mode product runs on the tiled kernel take their activation codes in
+        # the quantiser's widened format (same codes and scales, one byte per code): quantiser
+        # and GEMM of such a layer are the *_wide entry points, everywhere in this benchmark.
+        wide_d = [B.w4a4_takes_wide(Md, lin.N, lin.K) for lin in lins]
+        wide_v = [B.w4a4_takes_wide(Mv, lin.N, lin.K) for lin in lins]
+        qa8 = [torch.empty((Md, lin.K), dtype=torch.int8, device=dev) if w else None for lin, w in zip(lins, wide_d)]
+        qav8 = [torch.empty((Mv, lin.K), dtype=torch.int8, device=dev) if w else None for lin, w in zip(lins, wide_v)]
+
+        def quant(i, verify=False):
+            src, q, q8, s, wide = (xv, qav, qav8, sav, wide_v) if verify else (xd, qa, qa8, sa, wide_d)
+            if wide[i]:
+                B.quant_act_wide(src[i], q8[i], s[i])
+            else:
+                B.quant_act(src[i], q[i], s[i])
+
+        def w4a4(i, l, verify=False):
+            q, q8, s, y, wide = (qav, qav8, sav, yv, wide_v) if verify else (qa, qa8, sa, yd, wide_d)
+            if wide[i]:
+                B.gemm_w4a4_wide(blobs[i][l], q8[i], s[i], lins[i].N, y=y[i], workspace=ws)
+            else:
+                B.gemm_w4a4(blobs[i][l], q[i], s[i], lins[i].N, y=y[i], workspace=ws)
 
         def run_quant(M_is_verify=False):
-            src, q, s = (xv, qav, sav) if M_is_verify else (xd, qa, sa)
             for _ in range(L):
                 for i in range(nl):
-                    B.quant_act(src[i], q[i], s[i])
+                    quant(i, M_is_verify)
 
         def run_w4a4(M_is_verify=False):
-            q, s, y = (qav, sav, yv) if M_is_verify else (qa, sa, yd)
             for l in range(L):
-                for i, lin in enumerate(lins):
-                    B.gemm_w4a4(blobs[i][l], q[i], s[i], lin.N, y=y[i], workspace=ws)
+                for i in range(nl):
+                    w4a4(i, l, M_is_verify)
 
         def run_draft():
             for l in range(L):
-                for i, lin in enumerate(lins):
-                    B.quant_act(xd[i], qa[i], sa[i])
-                    B.gemm_w4a4(blobs[i][l], qa[i], sa[i], lin.N, y=yd[i], workspace=ws)
+                for i in range(nl):
+                    quant(i)
+                    w4a4(i, l)
 
         def run_w4a16(M_is_verify=True):
             x, y = (xv, yv) if M_is_verify else (xd, yd)
@@ -201,7 +220,7 @@ class Bench:
             def f():
                 for l in range(L):
                     if kind == "w4a4":
-                        B.gemm_w4a4(blobs[i][l], qa[i], sa[i], lin.N, y=yd[i], workspace=ws)
+                        w4a4(i, l)
                     else:
                         B.gemm_w4a16(blobs[i][l], xv[i], lin.N, y=yv[i], workspace=ws)
             return f
@@ -237,6 +256,8 @@ class Bench:
                     hbm_frac=round(ab(M, lin.N, lin.K) * L / t / 1e9 / HBM_PEAK_GBS, 4),
                     mfma_frac=round(fl * L / t / 1e12 / MFMA_PEAK_TFLOPS[kind], 4))
                 name = B.describe_kernel(kind == "w4a4", M, lin.N, lin.K)          # the profiler's symbol
+                if kind == "w4a4" and wide_d[i]:
+                    name = name.replace(", false>", ", true>")                     # (the instance that takes widened codes)
                 k = kernels.setdefault(name, dict(launches=0, seconds=0.0, bytes=0, flops=0, mode=kind))
                 k["launches"] += L
                 k["seconds"] += t
@@ -318,6 +339,8 @@ class Bench:
                                 GBps=round(v["bytes"] / v["seconds"] / 1e9, 1),
                                 TOPS=round(v["flops"] / v["seconds"] / 1e12, 2)) for k, v in kernels.items()},
             "calls": calls,
+            "widened_activation_format": {"draft_M": {lin.name: bool(w) for lin, w in zip(lins, wide_d)},
+                                          "verify_M": {lin.name: bool(w) for lin, w in zip(lins, wide_v)}},
             "same_shape": same,
         }
         if extras.get("rows_256_512"):
@@ -338,7 +361,8 @@ class Bench:
         extra = {}
         for Mx in Ms:
             xx = [torch.randn((Mx, lin.K), device=dev, generator=gen).half() for lin in lins]
-            qx = [B.quant_act(t) for t in xx]
+            wide = [B.w4a4_takes_wide(Mx, lin.N, lin.K) for lin in lins]
+            qx = [B.quant_act_wide(t) if w else B.quant_act(t) for t, w in zip(xx, wide)]
             yx = [torch.empty((Mx, lin.N), dtype=torch.float16, device=dev) for lin in lins]
             wsx = B.alloc_workspace(max([B.workspace_bytes(Mx, l.N, l.K) for l in lins] + [16]))
             Lx = min(L, 4)
@@ -347,7 +371,7 @@ class Bench:
                     def f(i=i, lin=lin, kind=kind):
                         for l in range(Lx):
                             if kind == "w4a4":
-                                B.gemm_w4a4(blobs[i][l], qx[i][0], qx[i][1], lin.N, y=yx[i], workspace=wsx)
+                                (B.gemm_w4a4_wide if wide[i] else B.gemm_w4a4)(blobs[i][l], qx[i][0], qx[i][1], lin.N, y=yx[i], workspace=wsx)
                             else:
                                 B.gemm_w4a16(blobs[i][l], xx[i], lin.N, y=yx[i], workspace=wsx)
                     t = self.time_runner(self.make_runner(f), 3, 1) / Lx

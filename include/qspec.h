@@ -191,6 +191,29 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa,
                     void* y_f16, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same quantiser and the same draft-mode product (paper Sec. 1, W4A4; Sec. 4.1,
+ * groups of 128) with the activation codes kept in a second device format for the shapes
+ * whose product runs on the tiled kernel (more than 64 tokens, or 48 on very wide layers):
+ * every code in a byte of its own, as int8 16 * code, 128 bytes per token row and group in
+ * the order of that kernel's LDS rows (byte b of the packed group's 64 bytes gives byte b
+ * = 16 * its low-nibble code and byte 64 + b = 16 * its high-nibble code).  The kernel then
+ * takes the codes global -> LDS directly instead of widening them in registers.  Codes and
+ * scales are those of qspec_quant_act bit for bit; only the storage differs.
+ *   qspec_w4a4_takes_wide   1 if qspec_gemm_w4a4_wide accepts this shape, else 0 (also 0
+ *                           for a shape the library refuses);
+ *   qspec_quant_act_wide    x_f16 fp16 [M,K];  qa8 out, M*K bytes;  sa out, fp32 [M,G];
+ *   qspec_gemm_w4a4_wide    arguments as qspec_gemm_w4a4 with qa8 in place of qa;
+ *                           QSPEC_ERR_UNSUPPORTED (nothing launched) for a shape whose
+ *                           product runs on a kernel that reads packed codes.
+ */
+int qspec_w4a4_takes_wide(int M, int N, int K, int group);
+int qspec_quant_act_wide(const void* x_f16, int M, int K, int group,
+                         int8_t* qa8, float* sa, void* stream);
+int qspec_gemm_w4a4_wide(const void* packed, const int8_t* qa8, const float* sa,
+                         int M, int N, int K, int group,
+                         void* y_f16, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Verify-mode product (paper Sec. 1: W4A16 dequantises the 4-bit weights to
  * fp16 at run time and multiplies with fp16 activations):
  *   y[m,n] = fp16( sum_k x[m,k] * qw[n,k] * sw[n, k/128] )       (fp32 sums)

@@ -18,6 +18,10 @@ Layout specification
            After all tiles: fp16 scales transposed to [G][N].
   acts   : row-major, 16 words per group; the word of codes k%128 in
            [32i + 8kb, +8) sits at word position 4kb + i of its group.
+  acts, widened (the second format of the activation quantiser, for the tiled
+           draft-mode kernel): row-major, 128 bytes per group, one int8 = 16 * code
+           per code.  The code that the packed format keeps in the low (high)
+           nibble of byte b of its group's 64 bytes sits at byte b (64 + b).
 """
 from __future__ import annotations
 
@@ -63,6 +67,41 @@ def act_bytes(codes: np.ndarray) -> np.ndarray:
     words = _words(codes).reshape(M, K // GROUP, 4, 4)          # [m, g, i, kb]  (k-word = 4i + kb)
     words = np.ascontiguousarray(words.transpose(0, 1, 3, 2))   # stored at position 4kb + i
     return words.astype("<u4").view(np.uint8).reshape(M, -1)
+
+
+def act_wide_bytes(codes: np.ndarray) -> np.ndarray:
+    """int8 codes [M, K] -> int8 [M, K] in the widened activation format (16 * code)."""
+    codes = np.asarray(codes)
+    M, K = codes.shape
+    if K % GROUP:
+        raise ValueError("K must be a multiple of 128")
+    G = K // GROUP
+    src = codes.astype(np.int16).reshape(M, G, GROUP)
+    out = np.zeros((M, G, GROUP), dtype=np.int16)
+    for i in range(4):
+        for kb in range(4):
+            for e in range(8):
+                k = 32 * i + 8 * kb + e                       # position inside the group
+                word = 4 * kb + i                             # word position in the packed group
+                b = 4 * word + POS[e] // 2                    # byte of the packed group holding this code
+                half = POS[e] % 2                             # 0: its low nibble, 1: its high nibble
+                out[:, :, b + 64 * half] = 16 * src[:, :, k]
+    return out.reshape(M, K).astype(np.int8)
+
+
+def decode_act_wide_bytes(qa8: np.ndarray) -> np.ndarray:
+    """Inverse of act_wide_bytes -> int8 codes [M, K]."""
+    qa8 = np.asarray(qa8, dtype=np.int8)
+    M, K = qa8.shape
+    G = K // GROUP
+    src = qa8.astype(np.int16).reshape(M, G, GROUP)
+    out = np.zeros((M, G, GROUP), dtype=np.int16)
+    for i in range(4):
+        for kb in range(4):
+            for e in range(8):
+                b = 4 * (4 * kb + i) + POS[e] // 2
+                out[:, :, 32 * i + 8 * kb + e] = src[:, :, b + 64 * (POS[e] % 2)] // 16
+    return out.reshape(M, K).astype(np.int8)
 
 
 def decode_act_bytes(qa: np.ndarray) -> np.ndarray:

@@ -23,6 +23,7 @@ EXPORTS = (
     "qspec_rmsnorm_quant", "qspec_silu_mul_quant", "qspec_hadamard_quant",
     "qspec_reorder_quant", "qspec_debug_set_plan",
     "qspec_gemm_w4a16_noalloc", "qspec_mlp_draft", "qspec_mlp_draft_workspace_bytes",
+    "qspec_w4a4_takes_wide", "qspec_quant_act_wide", "qspec_gemm_w4a4_wide",
 )
 
 
@@ -56,6 +57,12 @@ def lib() -> ctypes.CDLL:
     L.qspec_workspace_bytes.argtypes = [ci, ci, ci, ci]
     L.qspec_pack_weights.restype = ci
     L.qspec_pack_weights.argtypes = [vp, vp, ci, ci, ci, vp, vp]
+    L.qspec_w4a4_takes_wide.restype = ci
+    L.qspec_w4a4_takes_wide.argtypes = [ci, ci, ci, ci]
+    L.qspec_quant_act_wide.restype = ci
+    L.qspec_quant_act_wide.argtypes = [vp, ci, ci, ci, vp, vp, vp]
+    L.qspec_gemm_w4a4_wide.restype = ci
+    L.qspec_gemm_w4a4_wide.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
     L.qspec_unpack_weights.restype = ci
     L.qspec_unpack_weights.argtypes = [vp, ci, ci, ci, vp, vp, vp]
     L.qspec_quant_act.restype = ci
@@ -195,6 +202,25 @@ def quant_act(x: torch.Tensor, qa: torch.Tensor = None, sa: torch.Tensor = None,
     return qa, sa
 
 
+def w4a4_takes_wide(M: int, N: int, K: int, group: int = GROUP) -> bool:
+    """True when the draft-mode GEMM of this shape runs on the kernel that can take the widened
+    activation format (quant_act_wide -> gemm_w4a4_wide)."""
+    return bool(lib().qspec_w4a4_takes_wide(M, N, K, group))
+
+
+def quant_act_wide(x: torch.Tensor, qa8: torch.Tensor = None, sa: torch.Tensor = None, group: int = GROUP):
+    """x fp16 [M,K] -> (qa8 int8 [M,K] in the widened device format, sa fp32 [M,K/128])."""
+    M, K = x.shape
+    if qa8 is None:
+        qa8 = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if sa is None:
+        sa = torch.empty((M, max(K // group, 1)), dtype=torch.float32, device=x.device)
+    _check(lib().qspec_quant_act_wide(_dev(x, torch.float16, "x"), M, K, group,
+                                      _dev(qa8, torch.int8, "qa8"), _dev(sa, torch.float32, "sa"), _stream()),
+           "qspec_quant_act_wide")
+    return qa8, sa
+
+
 def _quant_outputs(M, K, group, device, qa, sa, h, want_h):
     if qa is None:
         qa = torch.empty((M, K // 2), dtype=torch.uint8, device=device)
@@ -271,6 +297,19 @@ def gemm_w4a4(packed: torch.Tensor, qa: torch.Tensor, sa: torch.Tensor, N: int,
                                  _dev(sa, torch.float32, "sa"), M, N, K, group,
                                  _dev(y, torch.float16, "y"), ws, ws_bytes, _stream()),
            "qspec_gemm_w4a4")
+    return y
+
+
+def gemm_w4a4_wide(packed: torch.Tensor, qa8: torch.Tensor, sa: torch.Tensor, N: int,
+                   y: torch.Tensor = None, workspace: torch.Tensor = None, group: int = GROUP) -> torch.Tensor:
+    M, K = qa8.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=qa8.device)
+    ws, ws_bytes = _workspace(M, N, K, group, workspace)
+    _check(lib().qspec_gemm_w4a4_wide(_dev(packed, torch.uint8, "packed"), _dev(qa8, torch.int8, "qa8"),
+                                      _dev(sa, torch.float32, "sa"), M, N, K, group,
+                                      _dev(y, torch.float16, "y"), ws, ws_bytes, _stream()),
+           "qspec_gemm_w4a4_wide")
     return y
 
 

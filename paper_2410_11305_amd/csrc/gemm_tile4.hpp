@@ -90,21 +90,31 @@ __device__ __forceinline__ void fmac_row_bcast_r(float& acc, float S, float t, i
 // do as well.
 __device__ __forceinline__ int act_swizzle(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-template <int PN, int PM, int WGN, int WGM, int OCC>
+template <int PN, int PM, int WGN, int WGM, int OCC, bool WIDE = false>
 __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileArgs p) {
   constexpr int kWaves = WGN * WGM;
   constexpr int kThreads = 64 * kWaves;
   constexpr int BM = 32 * PM * WGM;
   constexpr int NW = 3;                              // weight ring = LDS stages
   constexpr int kActBytes = BM * 128;
-  constexpr int kStageBytes = kActBytes + BM * 4;    // + sa[m] * 2^-8 of the group
   constexpr int kChunks = BM * 4;                    // 16-byte pieces of codes per group
   constexpr int U = (kChunks + kThreads - 1) / kThreads;
   constexpr int kTiles = PN * PM;
   static_assert(kChunks % kThreads == 0 || kChunks < kThreads, "whole passes, or one partial pass");
   static_assert(BM <= kThreads, "one thread per token row stages the activation scale");
   static_assert(PM % 2 == 0 && kTiles % 2 == 0, "the last tile of a group and the first of the next use different int32 tiles");
-  __shared__ __attribute__((aligned(16))) uint8_t lds[NW * kStageBytes];
+  // three stages, each an array of its own: with the widened activation format the codes come
+  // in by loads that write LDS directly, and the compiler then knows that a transfer into one
+  // stage never feeds a read of another (no wait between them)
+  // (and the token scales sa[m] * 2^-8 of a stage, written by ordinary LDS stores, sit in
+  // arrays apart from the codes: a store into an array that a transfer is filling would wait
+  // for that transfer)
+  __shared__ __attribute__((aligned(1024))) uint8_t stage0[kActBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t stage1[kActBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t stage2[kActBytes];
+  __shared__ float scale0[BM], scale1[BM], scale2[BM];
+  auto stage_ptr = [&](int i) -> uint8_t* { return i == 0 ? stage0 : i == 1 ? stage1 : stage2; };
+  auto scale_ptr = [&](int i) -> float* { return i == 0 ? scale0 : i == 1 ? scale1 : scale2; };
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -121,7 +131,7 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
 
   const rsrc_t r_codes = make_rsrc(p.codes, (uint32_t)((size_t)p.N * p.K / 2));
   const rsrc_t r_scales = make_rsrc(p.scalesT, (uint32_t)((size_t)p.N * G * 2));
-  const rsrc_t r_act = make_rsrc(p.act, (uint32_t)((size_t)p.M * p.K / 2));
+  const rsrc_t r_act = make_rsrc(p.act, (uint32_t)((size_t)p.M * p.K / (WIDE ? 1 : 2)));
   const rsrc_t r_sa = make_rsrc(p.sa, (uint32_t)((size_t)p.M * G * 4));
   // Work that does not exist gets bit 31 in its load offset (out of range: zeros, no
   // traffic), by arithmetic: a select between offsets tempts the compiler into a
@@ -151,7 +161,7 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
     }
   };
   auto store_x = [&](int stage) {                                                  // stage = (group index in the slice) % 3
-    uint8_t* base = lds + stage * kStageBytes;
+    uint8_t* base = stage_ptr(stage);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int idx = tid + u * kThreads;
@@ -167,7 +177,31 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
         *reinterpret_cast<v4i*>(base + row * 128 + ((s1 ^ sw) << 4)) = hi_first ? q.lo : q.hi;
       }
     }
-    if (tid < BM) *reinterpret_cast<float*>(base + kActBytes + tid * 4) = sas[stage] * 0.00390625f;   // 2^-8, exact
+    if (tid < BM) scale_ptr(stage)[tid] = sas[stage] * 0.00390625f;   // 2^-8, exact
+  };
+  // ---- activations in the widened format (WIDE): a token row's group is 128 bytes of int8
+  // in exactly the order of an LDS row, and goes global -> LDS without passing registers.
+  // A wave-wide transfer fills 1 KB = rows 8t .. 8t+7 linearly; wave w issues transfers
+  // t = w + u * kWaves.  Lane l writes slot l % 8 of row 8t + l / 8 and so must fetch slot
+  // (l % 8) ^ act_swizzle(row); act_swizzle(8t + r) = r ^ (t & 1) and t & 1 = w & 1 for every u
+  // because kWaves is even.  Rows past M lie past the end of the buffer (zeros or nothing:
+  // their outputs are never stored).
+  constexpr int kXfers = BM / 8;
+  constexpr int UD = kXfers / kWaves;
+  static_assert(!WIDE || (kXfers % kWaves == 0 && kWaves % 2 == 0), "whole transfers per wave; the swizzle of a transfer must not depend on u");
+  const int drow = lane >> 3;
+  const uint32_t xw_voff = (uint32_t)(m0 + 8 * wave + drow) * (uint32_t)p.K + (uint32_t)((((lane & 7) ^ drow ^ (wave & 1))) << 4);
+  auto dma_x = [&](int q, uint8_t* stage) {
+    const uint32_t gone = past_end(q);
+    const uint32_t gbase = (uint32_t)(g0 + q) * 128u;
+#pragma unroll
+    for (int u = 0; u < UD; ++u) {
+      const uint32_t off = (xw_voff + gbase + (uint32_t)(u * 8 * kWaves) * (uint32_t)p.K) | gone;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_act, (lds_ptr_t)(stage + (wave + u * kWaves) * 1024), 16, off, 0, 0, 0);
+    }
+  };
+  auto store_sa = [&](int stage) {
+    if (tid < BM) scale_ptr(stage)[tid] = sas[stage] * 0.00390625f;
   };
 
   // ---- weights: ring of NW groups; per 32-row pair two 16-byte pieces and the scale
@@ -234,24 +268,34 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
     const int slot = (st == 0 ? h : st == 1 ? h + 4 : st == 2 ? h + 2 : h + 6) ^ act_swizzle(row);
     a[st] = *reinterpret_cast<const v4i*>(xl + row * 128 + (slot << 4));
   };
-  auto read_scales = [&](const uint8_t* xl, int t, int buf) {
-    S[buf] = *reinterpret_cast<const float*>(xl + kActBytes + (mw0 + 32 * t + s_row) * 4);
+  auto read_scales = [&](const float* sl, int t, int buf) {
+    S[buf] = sl[mw0 + 32 * t + s_row];
   };
 
   // prologue: groups 0 and 1 into stages 0 and 1, group 2 requested (it stays in registers
   // until the top of group 0), the weight ring filled, the first operands read
   load_sa3(0);
-  load_x(0);
-  store_x(0);
-  load_x(1);
+  if constexpr (WIDE) {
+    dma_x(0, stage0);
+    dma_x(1, stage1);
 #pragma unroll
-  for (int d = 0; d < NW; ++d) load_w(d, d);
-  store_x(1);
-  load_x(2);
+    for (int d = 0; d < NW; ++d) load_w(d, d);
+    store_sa(0);
+    store_sa(1);
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+  } else {
+    load_x(0);
+    store_x(0);
+    load_x(1);
+#pragma unroll
+    for (int d = 0; d < NW; ++d) load_w(d, d);
+    store_x(1);
+    load_x(2);
+  }
   __syncthreads();
 #pragma unroll
-  for (int st = 0; st < 4; ++st) read_operand(lds, 0, st);
-  read_scales(lds, 0, 0);
+  for (int st = 0; st < 4; ++st) read_operand(stage0, 0, st);
+  read_scales(scale0, 0, 0);
 
   // Timetable of the activations of group q + 2: requested from memory at the top of group
   // q - 1, widened into stage (q + 2) % 3 at the top of group q (a whole group after the
@@ -260,11 +304,23 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
   // of a group's first token tile are fetched under the last tile of the group before).
   auto group_body = [&](auto slot_c, int q) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_c)::value;
-    const uint8_t* xl = lds + SLOT * kStageBytes;
-    const uint8_t* xl_next = lds + ((SLOT + 1) % NW) * kStageBytes;
-    store_x((SLOT + 2) % NW);                    // group q + 2; that stage was last read in group q - 1
-    if (SLOT == 0) load_sa3(q + 3);              // (its last scale, of group q + 2, has just been used)
-    load_x(q + 3);
+    const uint8_t* xl = stage_ptr(SLOT);
+    const uint8_t* xl_next = stage_ptr((SLOT + 1) % NW);
+    const float* sl = scale_ptr(SLOT);
+    const float* sl_next = scale_ptr((SLOT + 1) % NW);
+    if constexpr (WIDE) {
+      // group q + 2 straight into its stage (last read in group q - 1); it has the whole of
+      // this group to land, and the wait in front of this group's closing barrier counts the
+      // loads issued after it: the scale triple (slot 0 only) and the ring refill
+      dma_x(q + 2, stage_ptr((SLOT + 2) % NW));
+      __builtin_amdgcn_sched_barrier(0);
+      store_sa((SLOT + 2) % NW);
+      if (SLOT == 0) load_sa3(q + 3);
+    } else {
+      store_x((SLOT + 2) % NW);                  // group q + 2; that stage was last read in group q - 1
+      if (SLOT == 0) load_sa3(q + 3);            // (its last scale, of group q + 2, has just been used)
+      load_x(q + 3);
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     // operands of this group: four B operands per 32-row pair, the lane's weight scale
@@ -301,12 +357,15 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile4w_kernel(TileAr
         __builtin_amdgcn_sched_barrier(0);
       }
       // S[(t+1)&1] belonged to token tile t-1, whose last rescaling has just been issued
-      if (j == 0 && t + 1 < PM) read_scales(xl, t + 1, (t + 1) & 1);
+      if (j == 0 && t + 1 < PM) read_scales(sl, t + 1, (t + 1) & 1);
     }
     pend_sw = swf[PN - 1];
     pend_swc = swc[PN - 1];
     pend_S = S[(PM - 1) & 1];
-    read_scales(xl_next, 0, 0);                  // S[0] was token tile PM-2's: released
+    read_scales(sl_next, 0, 0);                  // S[0] was token tile PM-2's: released
+    // (loads complete in order; no store may sit between them, so the kernel must compile
+    // without register spills)
+    if constexpr (WIDE) __builtin_amdgcn_s_waitcnt(waitcnt_vm(3 * PN + (SLOT == 0 ? 1 : 0)));
     __syncthreads();
   };
 

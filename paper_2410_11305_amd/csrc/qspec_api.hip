@@ -519,9 +519,11 @@ inline size_t plan_ws_bytes(bool w4a4, const TilePlan& p) {
 }
 
 template <int PN, int PM, int WGN, int WGM, int OCC>
-int launch_tile4w_inst(const TileArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL((gemm_tile4w_kernel<PN, PM, WGN, WGM, OCC>), dim3(a.nb * a.mb * a.S),
-                     dim3(64 * WGN * WGM), 0, s, a);
+int launch_tile4w_inst(const TileArgs& a, bool wide, hipStream_t s) {
+  if (wide) hipLaunchKernelGGL((gemm_tile4w_kernel<PN, PM, WGN, WGM, OCC, true>), dim3(a.nb * a.mb * a.S),
+                               dim3(64 * WGN * WGM), 0, s, a);
+  else hipLaunchKernelGGL((gemm_tile4w_kernel<PN, PM, WGN, WGM, OCC, false>), dim3(a.nb * a.mb * a.S),
+                          dim3(64 * WGN * WGM), 0, s, a);
   return QSPEC_OK;
 }
 
@@ -533,16 +535,16 @@ int launch_tile16w_inst(const TileArgs& a, hipStream_t s) {
 }
 
 template <bool W4A4>
-int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s) {
+int launch_tile(const TilePlan& plan, TileArgs a, void* workspace, hipStream_t s, bool wide = false) {
   a.S = plan.S; a.nb = plan.nb; a.mb = plan.mb;
   a.tickets = static_cast<unsigned*>(workspace);
   a.ws = plan.S > 1 ? reinterpret_cast<float*>(static_cast<uint8_t*>(workspace) + kTicketBytes) : nullptr;
   if (W4A4) {
     switch (plan.shape) {
-      case 0: return launch_tile4w_inst<1, 4, 4, 1, 2>(a, s);
-      case 1: return launch_tile4w_inst<1, 2, 4, 1, 2>(a, s);
-      case 2: return launch_tile4w_inst<1, 2, 2, 1, 2>(a, s);
-      default: return launch_tile4w_inst<1, 4, 8, 1, 1>(a, s);
+      case 0: return launch_tile4w_inst<1, 4, 4, 1, 2>(a, wide, s);
+      case 1: return launch_tile4w_inst<1, 2, 4, 1, 2>(a, wide, s);
+      case 2: return launch_tile4w_inst<1, 2, 2, 1, 2>(a, wide, s);
+      default: return launch_tile4w_inst<1, 4, 8, 1, 1>(a, wide, s);
     }
   }
   switch (plan.shape) {
@@ -735,6 +737,23 @@ int qspec_quant_act(const void* x_f16, int M, int K, int group, uint8_t* qa, flo
   return launch_status();
 }
 
+int qspec_w4a4_takes_wide(int M, int N, int K, int group) {
+  if (check_shape(M, N, K, group) != QSPEC_OK) return 0;
+  return (!use_stream(true, M, N, K) && !use_generic()) ? 1 : 0;
+}
+
+int qspec_quant_act_wide(const void* x_f16, int M, int K, int group, int8_t* qa8, float* sa, void* stream) {
+  if (!x_f16 || !qa8 || !sa) return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, kTileRows, K, group)) return st;
+  if (misaligned(x_f16) || misaligned(qa8) || misaligned(sa)) return QSPEC_ERR_ALIGN;
+  if (int st = check_device()) return st;
+  const size_t n_words = (size_t)M * K / 8;
+  hipLaunchKernelGGL(quant_act_wide_kernel, dim3(blocks_for(n_words, 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(x_f16),
+                     reinterpret_cast<uint32_t*>(qa8), sa, n_words);
+  return launch_status();
+}
+
 int qspec_rmsnorm_quant(const void* x_f16, const void* weight_f16, float eps, int M, int K, int group,
                         int rotate, uint8_t* qa, float* sa, void* h_f16, void* stream) {
   if (!x_f16 || !weight_f16 || !qa || !sa) return QSPEC_ERR_NULL;
@@ -840,6 +859,26 @@ int qspec_gemm_w4a4(const void* packed, const uint8_t* qa, const float* sa, int 
     case 4: launch_w4a4<4>(a, s); break;
     default: launch_w4a4<8>(a, s); break;
   }
+  return launch_status();
+}
+
+int qspec_gemm_w4a4_wide(const void* packed, const int8_t* qa8, const float* sa, int M, int N, int K, int group,
+                         void* y_f16, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!packed || !qa8 || !sa || !y_f16) return QSPEC_ERR_NULL;
+  if (int st = check_shape(M, N, K, group)) return st;
+  if (misaligned(packed) || misaligned(qa8) || misaligned(sa) || misaligned(y_f16)) return QSPEC_ERR_ALIGN;
+  if (!qspec_w4a4_takes_wide(M, N, K, group)) return QSPEC_ERR_UNSUPPORTED;   // this shape runs on a kernel that reads packed codes
+  const size_t need = qspec_workspace_bytes(M, N, K, group);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return QSPEC_ERR_WORKSPACE;
+  if (int st = check_device()) return st;
+  TileArgs t{};
+  t.codes = static_cast<const uint4*>(packed);
+  t.scalesT = blob_scales(packed, N, K);
+  t.act = qa8;
+  t.sa = sa;
+  t.y = static_cast<uint16_t*>(y_f16);
+  t.M = M; t.N = N; t.K = K; t.G = K / kGroup;
+  if (int st = launch_tile<true>(plan_tile(true, M, N, K), t, workspace, static_cast<hipStream_t>(stream), true)) return st;
   return launch_status();
 }
 
@@ -1013,7 +1052,7 @@ int qspec_describe_kernel(int mode_w4a4, int M, int N, int K, int group, char* o
   } else {
     if (!use_generic()) {
       const TileShape& t = shape_of(mode_w4a4 != 0, plan_tile(mode_w4a4 != 0, M, N, K).shape);
-      if (mode_w4a4) snprintf(out, cap, "gemm_tile4w_kernel<%d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.OCC);
+      if (mode_w4a4) snprintf(out, cap, "gemm_tile4w_kernel<%d, %d, %d, %d, %d, false>", t.TN, t.TMW, t.WGN, t.WGM, t.OCC);
       else snprintf(out, cap, "gemm_tile16w_kernel<%d, %d, %d, %d, %d, %d, %d>", t.TN, t.TMW, t.WGN, t.WGM, t.NW, t.NS, t.OCC);
     } else if (mode_w4a4) snprintf(out, cap, "gemm_w4a4_generic<%d, 4, false>", pick_tm(M));
     else snprintf(out, cap, "gemm_w4a16_generic<%d, 4>", pick_tm(M));

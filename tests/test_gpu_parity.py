@@ -349,6 +349,16 @@ def test_benchmark_configuration(env, config):
         assert np.array_equal(P, orc.partials(q_ref, codes[n0:n0 + 64]))
         y4 = B.gemm_w4a4(blob, qa, sa, N).cpu().numpy()
         e4 = _rel_err_all_columns(y4, lambda cols: orc.gemm_w4a4_columns(q_ref, s_ref, codes, scales, cols), N)
+        if B.w4a4_takes_wide(cfg.draft_M, N, K):
+            # the widened activation format (what the benchmark's step feeds this layer): codes bit
+            # for bit against the oracle's layout, outputs against the oracle like the packed path
+            qa8, sa8 = B.quant_act_wide(dev(torch, xd))
+            assert np.array_equal(qa8.cpu().numpy(), lay.act_wide_bytes(q_ref))
+            assert np.array_equal(sa8.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+            y4w = B.gemm_w4a4_wide(blob, qa8, sa8, N).cpu().numpy()
+            e4w = _rel_err_all_columns(y4w, lambda cols: orc.gemm_w4a4_columns(q_ref, s_ref, codes, scales, cols), N)
+            print(f"   widened activations: rel err {e4w:.2e}", flush=True)
+            assert e4w <= TOL
 
         # verify: W4A16 at M = batch * (gamma + 1)
         xv = synth.activations(config, li, cfg.verify_M, K, verify=True)
@@ -367,6 +377,12 @@ def test_benchmark_configuration(env, config):
         assert np.array_equal(qv.cpu().numpy(), lay.act_bytes(qv_ref))
         y4v = B.gemm_w4a4(blob, qv, sv, N).cpu().numpy()
         e4v = _rel_err_all_columns(y4v, lambda cols: orc.gemm_w4a4_columns(qv_ref, sv_ref, codes, scales, cols), N)
+        if B.w4a4_takes_wide(cfg.verify_M, N, K):
+            qv8, sv8 = B.quant_act_wide(dev(torch, xv))
+            assert np.array_equal(qv8.cpu().numpy(), lay.act_wide_bytes(qv_ref))
+            y4vw = B.gemm_w4a4_wide(blob, qv8, sv8, N).cpu().numpy()
+            e4vw = _rel_err_all_columns(y4vw, lambda cols: orc.gemm_w4a4_columns(qv_ref, sv_ref, codes, scales, cols), N)
+            assert e4vw <= TOL
         print(f"   at the other mode's M: w4a16 {e16d:.2e}  w4a4 {e4v:.2e}", flush=True)
         assert e16d <= TOL and e4v <= TOL
         del blob, codes

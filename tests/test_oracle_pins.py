@@ -162,6 +162,58 @@ def test_act_bytes_roundtrip_and_word_order():
                     assert stored[m, 16 * g + 4 * kb + i] == words[m, 16 * g + 4 * i + kb]
 
 
+def test_act_wide_bytes_against_the_packed_bytes_nibble_by_nibble():
+    """The widened activation format is defined through the packed one: the code in the
+    low (high) nibble of byte b of a packed group is 16 * code at byte b (64 + b) of the
+    widened group.  Checked by a scalar walk over the packed bytes, a round trip, a
+    hand-written group and two planted mistakes (halves swapped; low and high taken
+    from the wrong nibble)."""
+    rng = np.random.default_rng(12)
+    codes = rng.integers(-8, 8, size=(3, 384), dtype=np.int8)
+    wide = lay.act_wide_bytes(codes)
+    assert wide.shape == (3, 384) and wide.dtype == np.int8
+    packed = lay.act_bytes(codes)
+
+    def signed(n):
+        return n - 16 if n >= 8 else n
+
+    def walk(packed, lo_first=True, swap_nibbles=False):
+        out = np.zeros((packed.shape[0], packed.shape[1] * 2), dtype=np.int8)
+        for m in range(packed.shape[0]):
+            for g in range(packed.shape[1] // 64):
+                for b in range(64):
+                    byte = int(packed[m, 64 * g + b])
+                    lo, hi = signed(byte & 15), signed(byte >> 4)
+                    if swap_nibbles:
+                        lo, hi = hi, lo
+                    out[m, 128 * g + (b if lo_first else 64 + b)] = 16 * lo
+                    out[m, 128 * g + (64 + b if lo_first else b)] = 16 * hi
+        return out
+
+    assert np.array_equal(wide, walk(packed))
+    assert not np.array_equal(wide, walk(packed, lo_first=False))
+    assert not np.array_equal(wide, walk(packed, swap_nibbles=True))
+    assert np.array_equal(lay.decode_act_wide_bytes(wide), codes)
+    # every group holds exactly its 128 codes, times 16
+    for m in range(3):
+        for g in range(3):
+            assert np.array_equal(np.sort(wide[m, 128 * g:128 * g + 128].astype(np.int16)),
+                                  np.sort(16 * codes[m, 128 * g:128 * g + 128].astype(np.int16)))
+    # by hand: codes k = 0..7 of a group are word (i = 0, kb = 0) -> packed word position 0, i.e.
+    # packed bytes 0..3 = (c2 c0), (c6 c4), (c3 c1), (c7 c5) as (high low) nibbles
+    one = np.zeros((1, 128), dtype=np.int8)
+    one[0, :8] = [1, 2, 3, 4, 5, 6, 7, -8]
+    w = lay.act_wide_bytes(one)[0].astype(np.int16)
+    assert w[0:4].tolist() == [16 * 1, 16 * 5, 16 * 2, 16 * 6]            # low nibbles: c0 c4 c1 c5
+    assert w[64:68].tolist() == [16 * 3, 16 * 7, 16 * 4, 16 * -8]         # high nibbles: c2 c6 c3 c7
+    assert int(np.count_nonzero(w)) == 8
+    # codes k = 8..15 (i = 0, kb = 1) go to word position 4: bytes 16..19 and 80..83
+    two = np.zeros((1, 128), dtype=np.int8)
+    two[0, 8:16] = [1, 2, 3, 4, 5, 6, 7, -8]
+    w = lay.act_wide_bytes(two)[0].astype(np.int16)
+    assert w[16:20].tolist() == [16, 80, 32, 96] and w[80:84].tolist() == [48, 112, 64, -128]
+
+
 # ================================================================ O2 quant_act
 def test_quant_act_hand_example_half_even():
     rows = dict(r.split(":", 1) for r in _read_golden("quant_act_rounding.txt"))
