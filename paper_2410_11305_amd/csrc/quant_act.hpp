@@ -29,13 +29,9 @@ __device__ inline float row16_max(float a) {
 // code word); 16 adjacent lanes (one row) own one group, so the absmax is a
 // 4-step fold inside the row and no LDS is needed.
 //
-// quantise_unit: v = this thread's 8 activations (fp16 values widened to
-// binary32), idx = index of its code word in the [M][K/8] word array.  Every lane
-// of the wavefront must call it (the shuffles); lanes that are not `live` pass
-// zeros and store nothing.  The number of words per row is a multiple of 16, so
-// a 16-lane group is entirely live or not.
-// The arithmetic alone: returns this thread's code word (8 nibbles in the device nibble
-// order) and the group's scale.  Every lane of the wavefront must call it.
+// quantise_word: the arithmetic alone.  v = this thread's 8 activations (fp16 values
+// widened to binary32); returns its code word (8 nibbles in the device nibble order)
+// and the group's scale.  Every lane of the wavefront must call it (the shuffles).
 __device__ inline uint32_t quantise_word(const float (&v)[8], float* s_out) {
   float a = 0.0f;
 #pragma unroll
@@ -55,6 +51,9 @@ __device__ inline uint32_t quantise_word(const float (&v)[8], float* s_out) {
   return w;
 }
 
+// quantise_unit: quantise and store in the packed format.  idx = index of the thread's code
+// word in the [M][K/8] word array; lanes that are not `live` pass zeros and store nothing.
+// The number of words per row is a multiple of 16, so a 16-lane group is entirely live or not.
 __device__ inline void quantise_unit(const float (&v)[8], bool live, size_t idx,
                                      uint32_t* __restrict__ qa_words, float* __restrict__ sa) {
   float s;
