@@ -425,8 +425,8 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
       // 384: 57.7 -> 50.0), or at least 90 % full in up to three K-slices of at least 21 groups
       // or four of at least 48 (28672 -> 8192 at 512 tokens, two slices: 179.6 -> 164.7; at 256,
       // four: 101.9 -> 93.8; 10240 x 8192 at 256, three: 47.4 -> 44.3; slices of 16 groups lose:
-      // 12288 x 4096 at 256 tokens 31.6 -> 34.5), or several rounds at least 85 % full (57344 x
-      // 8192 at 256 tokens: 188.3 -> 176.8; at 512, 3.5 rounds: equal; 1.3 rounds lose 6-8 %).
+      // 12288 x 4096 at 256 tokens 31.6 -> 34.5), or up to two rounds at least 85 % full (57344 x
+      // 8192 at 256 tokens: 188.3 -> 176.8; 1.3 rounds lose 6-8 %).
       const int mb128 = (M + 127) / 128;
       if (M > 96 && M * 4 >= mb128 * 128 * 3) {
         const int blocks3 = ((N + 255) / 256) * mb128;
@@ -438,8 +438,10 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
           const int full = blocks3 * c * 100;
           if (c == 1 ? full >= kNumCU * 60 : full >= kNumCU * 90) { shape = 3; S = c; }
         } else {
+          // (from three rounds on 95 %: 57344 x 8192 at 512 tokens, 3.5 rounds, equal with packed
+          // codes and 309 against 279 us on 128 x 128 blocks with the widened format)
           const int rounds3 = (blocks3 + kNumCU - 1) / kNumCU;
-          if (blocks3 * 100 >= rounds3 * kNumCU * 85) { shape = 3; S = 1; }
+          if (blocks3 * 100 >= rounds3 * kNumCU * (rounds3 <= 2 ? 85 : 95)) { shape = 3; S = 1; }
         }
       }
       s_chosen = true;
