@@ -599,12 +599,27 @@ class Bench:
             ygu = torch.empty((Md, 2 * Ii), dtype=torch.float16, device=dev)
             ydn = torch.empty((Md, lins[3].N), dtype=torch.float16, device=dev)
 
+            # (a consumer that runs on the tiled kernel gets its codes in the widened format,
+            # straight from the fused producer)
+            wide_gu = B.w4a4_takes_wide(Md, 2 * Ii, Kh)
+            wide_dn = B.w4a4_takes_wide(Md, lins[3].N, Ii)
+            q8_h = torch.empty((Md, Kh), dtype=torch.int8, device=dev) if wide_gu else None
+            q8_i = torch.empty((Md, Ii), dtype=torch.int8, device=dev) if wide_dn else None
+
             def mlp_fused():
                 for l in range(L):
-                    B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1])
-                    B.gemm_w4a4(blobs[i_gu][l], pq_h[0], pq_h[1], 2 * Ii, y=ygu, workspace=ws)
-                    B.silu_mul_quant(ygu, pq_i[0], pq_i[1])
-                    B.gemm_w4a4(blobs[3][l], pq_i[0], pq_i[1], lins[3].N, y=ydn, workspace=ws)
+                    if wide_gu:
+                        B.rmsnorm_quant(px, pw, synth.RMS_EPS, q8_h, pq_h[1], wide=True)
+                        B.gemm_w4a4_wide(blobs[i_gu][l], q8_h, pq_h[1], 2 * Ii, y=ygu, workspace=ws)
+                    else:
+                        B.rmsnorm_quant(px, pw, synth.RMS_EPS, pq_h[0], pq_h[1])
+                        B.gemm_w4a4(blobs[i_gu][l], pq_h[0], pq_h[1], 2 * Ii, y=ygu, workspace=ws)
+                    if wide_dn:
+                        B.silu_mul_quant(ygu, q8_i, pq_i[1], wide=True)
+                        B.gemm_w4a4_wide(blobs[3][l], q8_i, pq_i[1], lins[3].N, y=ydn, workspace=ws)
+                    else:
+                        B.silu_mul_quant(ygu, pq_i[0], pq_i[1])
+                        B.gemm_w4a4(blobs[3][l], pq_i[0], pq_i[1], lins[3].N, y=ydn, workspace=ws)
 
             def mlp_unfused():
                 for l in range(L):

@@ -124,8 +124,11 @@ int qspec_quant_act(const void* x_f16, int M, int K, int group,
  *               eps = 0 gives zeros);
  *   gate_up_f16 fp16 [M,2I], the gate in the first I columns; I a positive multiple of 128;
  *   qa, sa      out, as qspec_quant_act writes them for h ([M,K] resp. [M,I]);
- *   rotate      0, or 1: h is replaced by its rotation (qspec_hadamard_quant below, applied
- *               to the fp16 tensor h) before it is stored and quantised;
+ *   rotate      flag bits.  Bit 0 (value 1): h is replaced by its rotation
+ *               (qspec_hadamard_quant below, applied to the fp16 tensor h) before it is
+ *               stored and quantised.  Bit 1 (value 2): the codes are stored in the widened
+ *               format of qspec_quant_act_wide (qa then holds M*K resp. M*I bytes), for a
+ *               consumer that runs qspec_gemm_w4a4_wide.  Other bits: QSPEC_ERR_SHAPE;
  *   h_f16       out, fp16 [M,K] resp. [M,I], or NULL when the tensor itself is not
  *               needed (the draft pass needs only the codes).
  */

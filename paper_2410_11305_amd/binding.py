@@ -221,9 +221,10 @@ def quant_act_wide(x: torch.Tensor, qa8: torch.Tensor = None, sa: torch.Tensor =
     return qa8, sa
 
 
-def _quant_outputs(M, K, group, device, qa, sa, h, want_h):
+def _quant_outputs(M, K, group, device, qa, sa, h, want_h, wide=False):
     if qa is None:
-        qa = torch.empty((M, K // 2), dtype=torch.uint8, device=device)
+        qa = (torch.empty((M, K), dtype=torch.int8, device=device) if wide
+              else torch.empty((M, K // 2), dtype=torch.uint8, device=device))
     if sa is None:
         sa = torch.empty((M, max(K // group, 1)), dtype=torch.float32, device=device)
     if h is None and want_h:
@@ -233,13 +234,15 @@ def _quant_outputs(M, K, group, device, qa, sa, h, want_h):
 
 def rmsnorm_quant(x: torch.Tensor, weight: torch.Tensor, eps: float, qa: torch.Tensor = None,
                   sa: torch.Tensor = None, h: torch.Tensor = None, want_h: bool = False, rotate: bool = False,
-                  group: int = GROUP):
+                  group: int = GROUP, wide: bool = False):
     """RMSNorm (then, if `rotate`, the per-group Hadamard rotation) fused with the activation
-    quantiser: x fp16 [M,K], weight fp16 [K] -> (qa uint8 [M,K/2], sa fp32 [M,K/128], h fp16 [M,K] or None)."""
+    quantiser: x fp16 [M,K], weight fp16 [K] -> (qa uint8 [M,K/2], sa fp32 [M,K/128], h fp16 [M,K] or None);
+    `wide`: qa int8 [M,K] in the widened format instead."""
     M, K = x.shape
-    qa, sa, h = _quant_outputs(M, K, group, x.device, qa, sa, h, want_h)
+    qa, sa, h = _quant_outputs(M, K, group, x.device, qa, sa, h, want_h, wide)
     _check(lib().qspec_rmsnorm_quant(_dev(x, torch.float16, "x"), _dev(weight, torch.float16, "weight"),
-                                     float(eps), M, K, group, int(bool(rotate)), _dev(qa, torch.uint8, "qa"),
+                                     float(eps), M, K, group, int(bool(rotate)) | (2 if wide else 0),
+                                     _dev(qa, torch.int8 if wide else torch.uint8, "qa"),
                                      _dev(sa, torch.float32, "sa"),
                                      None if h is None else _dev(h, torch.float16, "h"), _stream()),
            "qspec_rmsnorm_quant")
@@ -247,13 +250,16 @@ def rmsnorm_quant(x: torch.Tensor, weight: torch.Tensor, eps: float, qa: torch.T
 
 
 def silu_mul_quant(gate_up: torch.Tensor, qa: torch.Tensor = None, sa: torch.Tensor = None,
-                   h: torch.Tensor = None, want_h: bool = False, rotate: bool = False, group: int = GROUP):
+                   h: torch.Tensor = None, want_h: bool = False, rotate: bool = False, group: int = GROUP,
+                   wide: bool = False):
     """SiLU(gate) * up (then, if `rotate`, the per-group Hadamard rotation) fused with the activation
-    quantiser: gate_up fp16 [M,2I] (gate first) -> (qa uint8 [M,I/2], sa fp32 [M,I/128], h fp16 [M,I] or None)."""
+    quantiser: gate_up fp16 [M,2I] (gate first) -> (qa uint8 [M,I/2], sa fp32 [M,I/128], h fp16 [M,I] or None);
+    `wide`: qa int8 [M,I] in the widened format instead."""
     M, I = gate_up.shape[0], gate_up.shape[1] // 2
-    qa, sa, h = _quant_outputs(M, I, group, gate_up.device, qa, sa, h, want_h)
-    _check(lib().qspec_silu_mul_quant(_dev(gate_up, torch.float16, "gate_up"), M, I, group, int(bool(rotate)),
-                                      _dev(qa, torch.uint8, "qa"), _dev(sa, torch.float32, "sa"),
+    qa, sa, h = _quant_outputs(M, I, group, gate_up.device, qa, sa, h, want_h, wide)
+    _check(lib().qspec_silu_mul_quant(_dev(gate_up, torch.float16, "gate_up"), M, I, group,
+                                      int(bool(rotate)) | (2 if wide else 0),
+                                      _dev(qa, torch.int8 if wide else torch.uint8, "qa"), _dev(sa, torch.float32, "sa"),
                                       None if h is None else _dev(h, torch.float16, "h"), _stream()),
            "qspec_silu_mul_quant")
     return qa, sa, h

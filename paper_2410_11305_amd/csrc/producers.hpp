@@ -112,10 +112,11 @@ __device__ inline void hadamard_row16(float (&v)[8], int l) {
 }
 
 // v: 8 fp16 values widened to binary32.  Rotates (if asked), rounds to fp16, stores the
-// fp16 tensor (if asked) and quantises.  Every lane of the wavefront calls it.
+// fp16 tensor (if asked) and quantises, into the packed or (wide) the widened code format.
+// Every lane of the wavefront calls it.
 __device__ inline void finish_unit(float (&v)[8], bool rotate, bool live, size_t idx,
                                    uint32_t* __restrict__ qa_words, float* __restrict__ sa,
-                                   uint4* __restrict__ h_out) {
+                                   uint4* __restrict__ h_out, bool wide = false) {
   v8h hh;
   if (rotate) {
     hadamard_row16(v, threadIdx.x & 15);
@@ -129,7 +130,8 @@ __device__ inline void finish_unit(float (&v)[8], bool rotate, bool live, size_t
     for (int e = 0; e < 8; ++e) hh[e] = (_Float16)v[e];                // v holds fp16 values: exact
   }
   if (h_out != nullptr && live) h_out[idx] = __builtin_bit_cast(uint4, hh);
-  quantise_unit(v, live, idx, qa_words, sa);
+  if (wide) quantise_unit_wide(v, live, idx, qa_words, sa);
+  else quantise_unit(v, live, idx, qa_words, sa);
 }
 
 // 1/sqrt(v) in binary64 to within a few units in the last place, v > 0 and normal: the
@@ -204,7 +206,7 @@ __global__ __launch_bounds__(kRowMaxThreads) void rmsnorm_quant_kernel(const uin
       const float t = (float)xh[e] * (float)wh[e];         // exact
       v8[e] = (float)(_Float16)rounded_f32(t * r);
     }
-    finish_unit(v8, rotate != 0, live, row0 + piece, qa_words, sa, h_out);
+    finish_unit(v8, (rotate & 1) != 0, live, row0 + piece, qa_words, sa, h_out, (rotate & 2) != 0);
   }
 }
 
@@ -231,7 +233,7 @@ __global__ __launch_bounds__(256) void silu_mul_quant_kernel(const uint4* __rest
     const float s = (float)(g / (1.0 + exp(-g)));
     v[e] = (float)(_Float16)rounded_f32(s * (float)uh[e]);
   }
-  finish_unit(v, rotate != 0, live, idx, qa_words, sa, h_out);
+  finish_unit(v, (rotate & 1) != 0, live, idx, qa_words, sa, h_out, (rotate & 2) != 0);
 }
 
 __global__ __launch_bounds__(256) void hadamard_quant_kernel(const uint4* __restrict__ x,

@@ -760,7 +760,7 @@ int qspec_rmsnorm_quant(const void* x_f16, const void* weight_f16, float eps, in
                         int rotate, uint8_t* qa, float* sa, void* h_f16, void* stream) {
   if (!x_f16 || !weight_f16 || !qa || !sa) return QSPEC_ERR_NULL;
   if (int st = check_shape(M, kTileRows, K, group)) return st;
-  if (!(eps >= 0.0f) || !(eps <= 3.0e38f) || (rotate != 0 && rotate != 1)) return QSPEC_ERR_SHAPE;
+  if (!(eps >= 0.0f) || !(eps <= 3.0e38f) || rotate < 0 || rotate > 3) return QSPEC_ERR_SHAPE;
   if (misaligned(x_f16) || misaligned(weight_f16) || misaligned(qa) || misaligned(sa) || misaligned(h_f16))
     return QSPEC_ERR_ALIGN;
   if (int st = check_device()) return st;
@@ -786,7 +786,7 @@ int qspec_silu_mul_quant(const void* gate_up_f16, int M, int I, int group,
                          int rotate, uint8_t* qa, float* sa, void* h_f16, void* stream) {
   if (!gate_up_f16 || !qa || !sa) return QSPEC_ERR_NULL;
   if (int st = check_shape(M, kTileRows, I, group)) return st;
-  if (rotate != 0 && rotate != 1) return QSPEC_ERR_SHAPE;
+  if (rotate < 0 || rotate > 3) return QSPEC_ERR_SHAPE;
   if (misaligned(gate_up_f16) || misaligned(qa) || misaligned(sa) || misaligned(h_f16)) return QSPEC_ERR_ALIGN;
   if (int st = check_device()) return st;
   const size_t n_words = (size_t)M * I / 8;

@@ -101,7 +101,7 @@ def test_producer_and_outlier_entries_validate_without_device():
     assert L.qspec_rmsnorm_quant(a, a, eps, 1, 192, 128, 0, a, a, None, None) == B.ERR_SHAPE
     assert L.qspec_rmsnorm_quant(a, a, -1.0, 1, 128, 128, 0, a, a, None, None) == B.ERR_SHAPE
     assert L.qspec_rmsnorm_quant(a, a, float("inf"), 1, 128, 128, 0, a, a, None, None) == B.ERR_SHAPE
-    assert L.qspec_rmsnorm_quant(a, a, eps, 1, 128, 128, 2, a, a, None, None) == B.ERR_SHAPE        # rotate is 0 or 1
+    assert L.qspec_rmsnorm_quant(a, a, eps, 1, 128, 128, 4, a, a, None, None) == B.ERR_SHAPE        # flag bits 0 and 1 only
     assert L.qspec_rmsnorm_quant(a, a + 8, eps, 1, 128, 128, 0, a, a, None, None) == B.ERR_ALIGN
     assert L.qspec_rmsnorm_quant(a, a, eps, 1, 128, 128, 0, a, a, a + 2, None) == B.ERR_ALIGN
     assert L.qspec_silu_mul_quant(None, 1, 128, 128, 0, a, a, None, None) == B.ERR_NULL

@@ -37,11 +37,22 @@ def check_against(torch, qa, sa, h, h_ref):
     assert np.array_equal(qa.cpu().numpy(), lay.act_bytes(q_ref))
 
 
+def check_wide_against(torch, qa8, sa, h_ref):
+    """The same launch asked for the widened code format: the same codes, one byte each."""
+    q_ref, s_ref = orc.quant_act(h_ref)
+    torch.cuda.synchronize()
+    assert np.array_equal(sa.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(qa8.cpu().numpy(), lay.act_wide_bytes(q_ref))
+
+
 def run_rmsnorm(env, x, w, eps, want_h=True, rotate=False):
     torch, B = env
     qa, sa, h = B.rmsnorm_quant(dev(torch, x), dev(torch, w), eps, want_h=want_h, rotate=rotate)
     h_ref = prod.rmsnorm_f16(x, w, eps)
-    check_against(torch, qa, sa, h, rot.hadamard128_f16(h_ref) if rotate else h_ref)
+    h_ref = rot.hadamard128_f16(h_ref) if rotate else h_ref
+    check_against(torch, qa, sa, h, h_ref)
+    qa8, sa8, _ = B.rmsnorm_quant(dev(torch, x), dev(torch, w), eps, rotate=rotate, wide=True)
+    check_wide_against(torch, qa8, sa8, h_ref)
     return qa, sa
 
 
@@ -49,7 +60,10 @@ def run_silu(env, gu, want_h=True, rotate=False):
     torch, B = env
     qa, sa, h = B.silu_mul_quant(dev(torch, gu), want_h=want_h, rotate=rotate)
     h_ref = prod.silu_mul_f16(gu)
-    check_against(torch, qa, sa, h, rot.hadamard128_f16(h_ref) if rotate else h_ref)
+    h_ref = rot.hadamard128_f16(h_ref) if rotate else h_ref
+    check_against(torch, qa, sa, h, h_ref)
+    qa8, sa8, _ = B.silu_mul_quant(dev(torch, gu), rotate=rotate, wide=True)
+    check_wide_against(torch, qa8, sa8, h_ref)
     return qa, sa
 
 
