@@ -60,7 +60,7 @@ typedef enum {
   QSPEC_ERR_ALIGN = 3,       /* a pointer is not 16-byte aligned              */
   QSPEC_ERR_WORKSPACE = 4,   /* workspace smaller than qspec_workspace_bytes  */
   QSPEC_ERR_HIP = 5,         /* the HIP runtime refused the launch            */
-  QSPEC_ERR_UNSUPPORTED = 6  /* not gfx950, or a forced plan has no kernel     */
+  QSPEC_ERR_UNSUPPORTED = 6  /* not gfx950; a forced plan has no kernel; a shape outside what a variant entry point takes */
 } qspec_status;
 
 /* Human-readable name of a status code (static storage, never NULL). */

@@ -669,7 +669,7 @@ const char* qspec_status_string(int status) {
     case QSPEC_ERR_ALIGN: return "pointer not 16-byte aligned";
     case QSPEC_ERR_WORKSPACE: return "workspace too small";
     case QSPEC_ERR_HIP: return "HIP runtime error";
-    case QSPEC_ERR_UNSUPPORTED: return "device is not gfx950, or a forced plan names a kernel instance that does not exist";
+    case QSPEC_ERR_UNSUPPORTED: return "device is not gfx950, a forced plan names a kernel instance that does not exist, or the shape lies outside what this variant entry point takes";
     default: return "unknown status";
   }
 }
