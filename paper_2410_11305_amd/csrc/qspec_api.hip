@@ -393,7 +393,19 @@ TilePlan plan_tile(bool w4a4, int M, int N, int K) {
         if (blocks[i] > places || (i == 0 && M <= 64)) continue;       // (a 128-token block is half empty at 64 tokens)
         int c = places / blocks[i];
         if (c > 4) c = 4;
-        while (c > 1 && G / c < 8) --c;
+        // (slices of fewer than 20 groups lose to the unsliced plan even at half the fill: 4096 x
+        // 4096 at 512 tokens, two slices of 16 groups 21.4 us, unsliced 18.8; 12288 x 4096 at 128:
+        // 21.1 against 19.5; slices of 21 groups win: 10240 x 8192 at 128 tokens, three slices 29.0 us,
+        // two 33.6, unsliced 39.3)
+        while (c > 1 && G / c < 20) --c;
+        // (but a chip left less than half full takes slices down to 12 groups, up to that half:
+        // 4096 x 4096 at 256 tokens, 128 blocks: 18.6 us unsliced, 15.7 in two slices of 16)
+        {
+          int c2 = places / 2 / blocks[i];
+          if (c2 > 4) c2 = 4;
+          while (c2 > 1 && G / c2 < 12) --c2;
+          if (c2 > c) c = c2;
+        }
         sl[i] = c;
         fill[i] = (double)blocks[i] * c / places;
       }
