@@ -45,6 +45,11 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 // leaving the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
 // expcnt 6:4, lgkmcnt 11:8).
 constexpr int waitcnt_vm(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4) | (0xF << 8); }
+// the same with lgkmcnt(0): every LDS (and scalar-memory) operation of the wave has completed too
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 0xF) | ((n >> 4) << 14) | (0x7 << 4); }
+#ifndef QSPEC_TILE16_EARLY
+#define QSPEC_TILE16_EARLY 1
+#endif
 
 template <int PN, int PM, int WGN, int WGM, int NW, int NS, int OCC>
 __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile16w_kernel(TileArgs p) {
@@ -172,29 +177,42 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile16w_kernel(TileA
   static_assert(Q >= P / 2, "at most two pieces between MFMAs");
   constexpr int PER = (P + Q - 1) / Q;         // pieces after each MFMA
 
+  // LDS reads run XB-1 k-steps ahead of the MFMAs that consume them: a k-step of a
+  // small wave tile is too short (PN*PM*32 cycles) to cover the LDS latency alone.
+  // EARLY (wave tiles of four or more MFMAs per k-step, reads one step ahead): the barrier
+  // that ends a group stands in front of its LAST k-step instead of behind it.  By then a
+  // wave has issued every LDS read of the group, so the barrier certifies what the one at
+  // the end did (everyone is done with this stage, everyone's transfers of the next stage
+  // have landed), and the first operands of the next group are read under the last
+  // k-step's MFMAs: no wave starts a group by waiting for LDS with nothing to issue.
+  constexpr bool EARLY = QSPEC_TILE16_EARLY && PN * PM >= 4;
+  constexpr int XB = EARLY ? 2 : (PN * PM >= 8 ? 2 : (PN * PM >= 4 ? 3 : 4));
+  uint4 xb[XB][PM];
+  auto read_step_from = [&](const uint8_t* xl, int s, uint4 (&dst)[PM]) {
+    const int c = 4 * (s >> 1) + 2 * (s & 1) + h;      // this lane's k-chunk of step s
+#pragma unroll
+    for (int t = 0; t < PM; ++t) {
+      const int row = mw0 + 32 * t + m32;
+      dst[t] = *reinterpret_cast<const uint4*>(xl + row * 256 + ((c ^ (row & 15)) << 4));
+    }
+  };
+  if constexpr (EARLY) read_step_from(xs0, 0, xb[0]);      // group 0, k-step 0
+
   auto group_body = [&](auto slot_c, int g) __attribute__((always_inline)) {
     constexpr int SLOT = decltype(slot_c)::value;
     constexpr int NEXT = (SLOT + 1) % NW;
     const uint8_t* xl = stage_ptr(SLOT % NS);
+    const uint8_t* xl_next = stage_ptr((SLOT + 1) % NS);
     uint8_t* xnext = stage_ptr((SLOT + D) % NS);   // last read in the group before this one
-    // LDS reads run XB-1 k-steps ahead of the MFMAs that consume them: a k-step of a
-    // small wave tile is too short (PN*PM*32 cycles) to cover the LDS latency alone
-    constexpr int XB = PN * PM >= 8 ? 2 : (PN * PM >= 4 ? 3 : 4);
-    uint4 xb[XB][PM];
-    auto read_step = [&](int s, uint4 (&dst)[PM]) {
-      const int c = 4 * (s >> 1) + 2 * (s & 1) + h;      // this lane's k-chunk of step s
-#pragma unroll
-      for (int t = 0; t < PM; ++t) {
-        const int row = mw0 + 32 * t + m32;
-        dst[t] = *reinterpret_cast<const uint4*>(xl + row * 256 + ((c ^ (row & 15)) << 4));
-      }
-    };
+    auto read_step = [&](int s, uint4 (&dst)[PM]) { read_step_from(xl, s, dst); };
     auto word_of_step = [&](int d, int j, int s) -> uint32_t {
       const uint4& q = (s & 1) ? whi[d][j] : wlo[d][j];
       return word_of(q, s >> 1);
     };
+    if constexpr (!EARLY) {
 #pragma unroll
-    for (int s = 0; s < XB - 1; ++s) read_step(s, xb[s]);
+      for (int s = 0; s < XB - 1; ++s) read_step(s, xb[s]);
+    }
     __builtin_amdgcn_sched_barrier(0);
     v2h wa[2][PN][4];                            // k-step s lives in wa[s & 1]
 #pragma unroll
@@ -204,6 +222,15 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile16w_kernel(TileA
 #pragma unroll
     for (int s = 0; s < 8; ++s) {
       if (s + XB - 1 < 8) read_step(s + XB - 1, xb[(s + XB - 1) % XB]);
+      if constexpr (EARLY) {
+        if (s == 7) {
+          // (the count as at the end of the group: the ring refill of k-step 6 is the youngest
+          // load; lgkmcnt(0): this wave's reads of the stage have completed, not only issued)
+          __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((D - 1) * (U + 3 * PN) + 3 * PN));
+          __builtin_amdgcn_s_barrier();
+          read_step_from(xl_next, 0, xb[0]);
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
       if (s == 1) {
         // every wave has passed the barrier that ended the last group reading that
@@ -255,8 +282,10 @@ __global__ __launch_bounds__(64 * WGN * WGM, OCC) void gemm_tile16w_kernel(TileA
     // order: at most that many outstanding means those activations have landed.  (No
     // store may sit between them - stores complete out of order with loads - so this
     // kernel must compile without register spills in the loop.)
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm((D - 1) * (U + 3 * PN) + 3 * PN));
-    __builtin_amdgcn_s_barrier();
+    if constexpr (!EARLY) {
+      __builtin_amdgcn_s_waitcnt(waitcnt_vm((D - 1) * (U + 3 * PN) + 3 * PN));
+      __builtin_amdgcn_s_barrier();
+    }
   };
 
   for (int q = 0; q < ng; q += NW) {
