@@ -33,6 +33,9 @@
 //     writes land under that group's arithmetic); one barrier per group.  Row layout: 8 slots of 16 bytes (slot kb: low nibbles of k-block kb,
 //     slot 4+kb: high nibbles), slot index xor-ed with act_swizzle(row) so that the
 //     operand reads and the staging writes are free of bank conflicts.
+//     With the quantiser's widened format (WIDE: one int8 = 16 * code per code, 128 bytes
+//     per row and group in exactly this row layout) the rows go global -> LDS by loads
+//     that write LDS directly, two groups ahead: no widening, no staging registers.
 //   - Weights and their scales: straight into registers in MFMA operand layout
 //     through a ring of three groups (slots named statically: the group loop is
 //     unrolled three times, which also fixes the LDS stage of a group).
